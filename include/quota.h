@@ -1,0 +1,293 @@
+/*
+ * libquota -- C ABI of the MI355X (gfx950) implementation of the QUOTA hot
+ * path: a W4A4 language-model prefill layer that scores, top-k prunes and
+ * compacts visual tokens inside the layer and writes a 4-bit KV cache.
+ *
+ * General rules
+ *   - Every pointer named in a signature is a DEVICE pointer owned by the
+ *     caller unless it is marked "host".  The library allocates no device
+ *     memory; scratch comes from a caller workspace whose size the
+ *     *_workspace_bytes call reports.
+ *   - Descriptor structs (quota_weights, quota_kv_cache, quota_layer,
+ *     quota_state, quota_score_params, quota_taps) live in HOST memory.
+ *   - `stream` is a hipStream_t passed as void*.  Calls only enqueue work on
+ *     that stream; none synchronises.  Calls on one stream are ordered.
+ *   - Every call returns QUOTA_OK or a negative error code and enqueues
+ *     nothing when it returns an error.  No exceptions cross the boundary.
+ *   - fp16 = IEEE binary16.  int4 data is two's complement, two codes per
+ *     byte, element 2j in bits 0-3 and element 2j+1 in bits 4-7.
+ *   - Weight groups are 128 input channels (QUOTA_GROUP_W), KV groups are 64
+ *     channels of one head (QUOTA_GROUP_KV).
+ */
+#ifndef QUOTA_H
+#define QUOTA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QUOTA_GROUP_W 128
+#define QUOTA_GROUP_KV 64
+
+enum {
+    QUOTA_OK = 0,
+    QUOTA_ERR_NULL = -1,        /* a required pointer is null                      */
+    QUOTA_ERR_INVALID_ARG = -2, /* negative size, bad flag, bad percentile ...     */
+    QUOTA_ERR_SHAPE = -3,       /* shape the kernels do not support (see each call) */
+    QUOTA_ERR_CAPACITY = -4,    /* KV cache or workspace too small                 */
+    QUOTA_ERR_HIP = -5          /* the HIP runtime reported a launch error         */
+};
+
+const char *quota_strerror(int code);
+int quota_version(void);
+
+/* ---- W4 weights (unified low-bit execution form, Method overview) ------- */
+
+/* One packed W4 matrix y = x W^T, W logically [N][K].  `packed` holds the
+ * int4 codes in the library's GEMM layout ([K/128 groups][N rows][64 bytes],
+ * K zero-padded to a multiple of 128), `scales` the fp16 group scales in
+ * [group][N] order.  Both buffers are caller-allocated device memory of
+ * quota_weights_packed_bytes / quota_weights_scale_bytes bytes. */
+typedef struct quota_weights {
+    int N;
+    int K;
+    void *packed;
+    void *scales;
+} quota_weights;
+
+size_t quota_weights_packed_bytes(int N, int K);
+size_t quota_weights_scale_bytes(int N, int K);
+
+/* Symmetric int4 group quantization of an fp32 matrix w [N][K] (row-major,
+ * device): per (row, 128-channel group) a = max|w|, scale = fp16(a/7) (1 when
+ * that is zero), code = clamp(rne(w / scale), -8, 7).  Writes plain row-major
+ * outputs: codes int8 [N][K] (one code per byte) and scales fp16
+ * [N][ceil(K/128)].  Requires N, K > 0. */
+int quota_quantize_weights(const float *w, int N, int K, int8_t *codes,
+                           void *scales_f16, void *stream);
+
+/* Repack plain row-major codes (int8, one per byte, values in [-8,7]) and
+ * scales (fp16 [N][ceil(K/128)]) into W->packed / W->scales.  Requires
+ * N % 64 == 0 and K % 32 == 0 (QUOTA_ERR_SHAPE otherwise). */
+int quota_pack_weights(const int8_t *codes, const void *scales_f16,
+                       const quota_weights *W, void *stream);
+
+/* ---- per-token int4 activation quantizer (the quantizer Q of Eq. 6) ----- */
+
+/* x fp16 [M][d] with row stride ldx (elements).  Per row: a = max|x|,
+ * scale = a/7 (fp32; 1 if a == 0), code = clamp(rne(x * (7/a)), -8, 7).
+ * q_packed uint8 [M][d/2]; scale fp32 [M].  Optional side outputs per row:
+ * sumsq_opt = sum x^2 (m_mag^2) and ressq_opt = sum (code*scale - x)^2
+ * (m_res^2), both accumulated in fp64 and rounded to fp32.
+ * Requires d % 8 == 0, d <= 16384, ldx >= d and ldx % 8 == 0. */
+int quota_quantize_act(const void *x_f16, int M, int d, int ldx,
+                       uint8_t *q_packed, float *scale, float *sumsq_opt,
+                       float *ressq_opt, void *stream);
+
+/* Fused RMSNorm + quantizer used in front of the QKV and gate/up GEMMs:
+ * h = fp16((x * rsqrt(mean(x^2) + eps)) * gamma), then the quantizer above
+ * applied to h.  The side outputs refer to the RAW row x (the hidden state
+ * entering the layer, which is the v_i of Eq. 6): sumsq_opt = sum x^2,
+ * ressq_opt = residual of quantizing x itself.  h_opt (fp16 [M][d]) receives
+ * the normalised row when not null.  gamma is fp32 [d]. */
+int quota_rmsnorm_quantize_act(const void *x_f16, int M, int d, int ldx,
+                               const float *gamma, float eps,
+                               uint8_t *q_packed, float *scale,
+                               float *sumsq_opt, float *ressq_opt,
+                               void *h_opt, void *stream);
+
+/* Fused SwiGLU product + quantizer in front of the down projection:
+ * z = fp16(silu(gate) * up) with gate = gu[:, 0:F], up = gu[:, F:2F]
+ * (gu fp16 [M][2F] dense), then the quantizer applied to z.  z_opt receives
+ * z; z_inject_opt, when not null, replaces the computed z (parity harness).
+ * Requires F % 8 == 0 and F <= 16384. */
+int quota_silu_mul_quantize_act(const void *gu_f16, int M, int F,
+                                uint8_t *q_packed, float *scale, void *z_opt,
+                                const void *z_inject_opt, void *stream);
+
+/* ---- W4A4 GEMM (W4A4 linear operators of the language model) ------------ */
+
+/* y[m][n] = fp16( sa[m] * sum_g sw[n][g] * acc_g[m][n]  (+ residual[m][n]) ),
+ * acc_g the exact int32 dot product of the int4 codes over group g; groups
+ * are combined in fp32 with one fused multiply-add each, in ascending order.
+ * qa uint8 [M][K/2] packed (row stride K/2), sa fp32 [M], y fp16 [M][ldy],
+ * residual_opt fp16 [M][ldr].  acc_i32_opt int32 [M][N] (dense) receives the
+ * exact full-K integer dot product (parity harness; slower kernel).
+ * Requires M >= 0, ldy >= N; W as accepted by quota_pack_weights. */
+int quota_w4a4_gemm(const uint8_t *qa, const float *sa, int M,
+                    const quota_weights *W, void *y_f16, int ldy,
+                    const void *residual_opt, int ldr, int32_t *acc_i32_opt,
+                    void *stream);
+
+/* ---- RoPE + 4-bit KV quantization (quantized KV cache) ------------------ */
+
+/* 4-bit KV cache of ONE layer.  Row r of sequence b lives at index
+ * b*capacity + r.  k_codes/v_codes uint8 [B][capacity][H*dh/2];
+ * k_scales/v_scales fp16 [B][capacity][H*dh/64].  `len` (host field, same
+ * for every sequence) is advanced by the append calls. */
+typedef struct quota_kv_cache {
+    int B, capacity, H, dh;
+    int len;
+    uint8_t *k_codes;
+    void *k_scales;
+    uint8_t *v_codes;
+    void *v_scales;
+} quota_kv_cache;
+
+/* Rotates q and k (rotate-half pairing (i, i+dh/2)) by the angle tables
+ * cosT/sinT (fp32 [n_pos][dh/2]) at each token's ORIGINAL position id
+ * pos[row] -- positions stay aligned with tokens after pruning (compaction
+ * paragraph after Eq. 9) -- then quantizes k (post-RoPE, rounded to fp16) and
+ * v per (token, head, 64-channel group): a = max|x|, s = fp16(a/7) (1 if
+ * zero), code = clamp(rne(x * (1/s)), -8, 7).
+ * qkv fp16 [M][3*H*dh] (q | k | v), pos int32 [M] with 0 <= pos < n_pos.
+ * Outputs for all M rows: q_rot fp16 [M][H*dh]; khat / vhat fp16 [M][H*dh] =
+ * fp16(code * s), the values attention sees; staged codes uint8 [M][H*dh/2]
+ * and scales fp16 [M][H*dh/64] for k and v.  Requires dh == 64 or 128. */
+int quota_rope_kv_quant(const void *qkv_f16, int M, int H, int dh,
+                        const int32_t *pos, const float *cosT,
+                        const float *sinT, int n_pos, void *q_rot_f16,
+                        void *khat_f16, void *vhat_f16, uint8_t *k_codes,
+                        void *k_scales, uint8_t *v_codes, void *v_scales,
+                        void *stream);
+
+/* Quantizes the rows keep_rows[b][0..n_keep) of k and v (fp16 [B][N][H*dh],
+ * k already rotated) exactly as above and appends them to `cache` at row
+ * cache->len, then advances cache->len by n_keep.  keep_rows int32
+ * [B][n_keep] (device) are row indices inside each sequence; null means rows
+ * 0..n_keep-1.  K/V are stored for retained tokens only.
+ * QUOTA_ERR_CAPACITY if len + n_keep > capacity (nothing is written). */
+int quota_kv_quant_append(const void *k_f16, const void *v_f16, int B, int N,
+                          int H, int dh, const int32_t *keep_rows, int n_keep,
+                          quota_kv_cache *cache, void *stream);
+
+/* ---- attention over the 4-bit K/V + column masses (Eq. 6 cues) ---------- */
+
+size_t quota_attention_workspace_bytes(int B, int N, int H, int dh);
+
+/* Causal softmax attention of q (fp16 [B][N][H*dh], rotated) over khat / vhat
+ * (fp16 [B][N][H*dh], the dequantized 4-bit K/V of the same rows), scores
+ * scaled by 1/sqrt(dh), fp16 MFMA with fp32 softmax.  o fp16 [B][N][H*dh].
+ * Also the two attention cues of Eq. 6 for each visual key i in
+ * [vis_begin, vis_begin+Nv): cm_inter[b][i] = mean over heads of the total
+ * probability that text queries put on key i, cm_intra the same for visual
+ * queries (fp32 [B][Nv]); pass both null to skip the cue pass.
+ * ws: quota_attention_workspace_bytes bytes.  Requires dh == 64 or 128. */
+int quota_attention_prefill(const void *q_f16, const void *khat_f16,
+                            const void *vhat_f16, int B, int N, int H, int dh,
+                            int vis_begin, int Nv, void *o_f16,
+                            float *cm_inter, float *cm_intra, void *ws,
+                            void *stream);
+
+/* ---- scoring (Eq. 6-8) and budgeted top-k (Eq. 5, Eq. 9) ---------------- */
+
+typedef struct quota_score_params {
+    float w_m, w_c, w_s, w_r; /* weights of mag, inter, intra, res (Eq. 8)   */
+    int pct_lo, pct_hi;       /* percentiles of the robust normalisation G   */
+} quota_score_params;
+
+/* Table 5 default row: inter 45 %, mag 25 %, intra 10 %, quant 20 %;
+ * percentiles 10 / 90. */
+void quota_score_params_default(quota_score_params *p);
+
+/* Composite score of every visual token from the four Eq. 6 metrics given as
+ * arrays [B][Nv] fp32: sumsq (= m_mag^2) and ressq (= m_res^2) as produced by
+ * the quantizer's side outputs, cm_inter and cm_intra as produced by the
+ * attention call.  Per sequence and metric, G (Eq. 7) clips to the
+ * nearest-rank percentiles (rank = (p*(Nv-1)+50)/100 on the ascending order)
+ * and rescales to [0,1] (0.5 for a flat metric); then
+ * score = ((w_m*g_mag + w_c*g_inter) + w_s*g_intra) + w_r*g_res in fp32.
+ * normed_opt receives the normalised metrics [4][B][Nv] (mag, inter, intra,
+ * res).  Requires 0 <= pct_lo <= pct_hi <= 100, Nv <= 4096. */
+int quota_score_tokens(const float *sumsq, const float *ressq,
+                       const float *cm_inter, const float *cm_intra, int B,
+                       int Nv, const quota_score_params *p, float *score,
+                       float *normed_opt, void *stream);
+
+/* Same score, with the two vector metrics computed here from the visual
+ * token representations v fp16 [B][Nv][d] (row stride ldv, sequence stride
+ * stride_b, both in elements).  ws: 2*B*Nv floats. */
+int quota_score_tokens_from_hidden(const void *v_f16, int B, int Nv, int d,
+                                   int ldv, long stride_b,
+                                   const float *cm_inter,
+                                   const float *cm_intra,
+                                   const quota_score_params *p, float *score,
+                                   float *normed_opt, void *ws, void *stream);
+
+/* Deterministic TopK (Eq. 9): the min(K, Nv) largest scores of each sequence,
+ * ties broken towards the lower index, emitted in ascending index order.
+ * score fp32 [B][Nv]; keep_idx int32 [B][min(K,Nv)].  K is the integer budget
+ * K_l = ceil(r_l * V0) (Eq. 5) -- the rounding is the recipe's job.  NaN
+ * scores rank lowest.  Requires Nv <= 4096, K >= 0. */
+int quota_topk_prune(const float *score, int B, int Nv, int K,
+                     int32_t *keep_idx, void *stream);
+
+/* ---- the whole layer ---------------------------------------------------- */
+
+typedef struct quota_layer {
+    int H, dh, F;                /* d = H*dh                                  */
+    float eps;
+    const float *gamma1, *gamma2; /* fp32 [d]                                 */
+    quota_weights qkv;           /* [3d][d], rows q | k | v                   */
+    quota_weights o;             /* [d][d]                                    */
+    quota_weights gu;            /* [2F][d], rows gate | up                   */
+    quota_weights down;          /* [d][F]                                    */
+    const float *cosT, *sinT;    /* fp32 [n_pos][dh/2]                        */
+    int n_pos;
+} quota_layer;
+
+/* Layer state (host struct, device buffers).  On entry x holds B sequences of
+ * N = vis_begin + Nv + Nt_after rows each (visual tokens in rows
+ * [vis_begin, vis_begin+Nv)), pos their original position ids.  On return
+ * x_out / pos_out hold the compacted sequences (kept visual tokens + every
+ * text token, original order) and N, Nv are updated. */
+typedef struct quota_state {
+    int B, N, vis_begin, Nv;
+    const void *x;       /* fp16 [B][N][d]                                    */
+    const int32_t *pos;  /* int32 [B][N]                                      */
+    void *x_out;         /* fp16 [B][n_keep][d]                               */
+    int32_t *pos_out;    /* int32 [B][n_keep]                                 */
+} quota_state;
+
+/* Optional dump / inject points for the parity harness.  Every pointer may be
+ * null.  Dumps receive the tensor the layer computed; injects replace it
+ * before the next step consumes it. */
+typedef struct quota_taps {
+    void *qkv;            /* fp16 [B*N][3d]                                   */
+    void *q_rot;          /* fp16 [B*N][d]                                    */
+    void *o;              /* fp16 [B*N][d] attention output                   */
+    float *sumsq, *ressq; /* [B][Nv]                                          */
+    float *cm_inter, *cm_intra, *score; /* [B][Nv]                            */
+    int32_t *keep_idx;    /* [B][min(K,Nv)]                                   */
+    int32_t *rows;        /* [B][n_keep] kept row ids                         */
+    void *x1;             /* fp16 [B*n_keep][d]                               */
+    void *gu;             /* fp16 [B*n_keep][2F]                              */
+    void *z;              /* fp16 [B*n_keep][F]                               */
+    const void *inject_o;        /* fp16 [B*N][d]                             */
+    const float *inject_cm_inter, *inject_cm_intra; /* [B][Nv]                */
+    const void *inject_z;        /* fp16 [B*n_keep][F]                        */
+} quota_taps;
+
+size_t quota_prefill_workspace_bytes(const quota_layer *L, int B, int N);
+
+/* One decoder layer of the deployed low-bit forward pass (Method overview;
+ * Eq. 5-9 and the compaction paragraph): RMSNorm + int4 activations + W4A4
+ * QKV, RoPE, 4-bit K/V for all N tokens, causal attention over the 4-bit
+ * K/V, the four cues, G, score fusion, top-K_l over the visual tokens, then
+ * compaction: kept rows of the hidden state and positions move on, their 4-bit
+ * K/V rows are appended to `cache` (this layer's cache), and the output
+ * projection and SwiGLU FFN (all token-wise) run on the kept rows only.
+ * K_l >= Nv keeps every token.  ws: quota_prefill_workspace_bytes bytes.
+ * Errors: as the calls above; QUOTA_ERR_CAPACITY when the cache cannot take
+ * n_keep more rows. */
+int quota_prefill_layer(const quota_layer *L, quota_state *st, int K_l,
+                        const quota_score_params *p, quota_kv_cache *cache,
+                        const quota_taps *taps_opt, void *ws, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QUOTA_H */

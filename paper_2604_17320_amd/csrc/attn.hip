@@ -1,0 +1,288 @@
+// Causal prefill attention over the dequantized 4-bit K/V (fp16 MFMA, fp32
+// online softmax) and the attention-cue pass of Eq. 6 (column masses).
+//
+// Pass 1 works on transposed tiles so that every softmax statistic is a
+// per-lane scalar: S^T = K Q^T puts the query on the lane (column) and the
+// keys on the accumulator registers; the probabilities then feed
+// O^T += V^T P^T straight from those registers (their register->key mapping is
+// exactly the k-slot mapping of the B operand of v_mfma_f32_32x32x8_f16).
+//
+// Pass 2 owns key columns instead: S = Q K^T puts the key on the lane, so the
+// column sums over queries are in-lane adds in a fixed order (deterministic,
+// no atomics).  It needs the final log-sum-exp of every query row from pass 1.
+#include "common.h"
+#include "internal.h"
+
+namespace {
+
+constexpr int KT = 64;       // keys per tile (pass 1), queries per tile (pass 2)
+
+template <int DH>
+struct AttnSmem {
+    f16 k[KT][DH + 4];       // row stride 2 banks apart: conflict-free 8-byte reads
+    f16 vt[DH][KT + 4];      // V transposed: [channel][key]
+};
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(
+    const f16 *__restrict__ q, const f16 *__restrict__ khat, const f16 *__restrict__ vhat, int N,
+    int H, f16 *__restrict__ o, float *__restrict__ lse2, float scale_log2)
+{
+    constexpr int T = DH / 8;        // k-steps of the QK product
+    constexpr int DB = DH / 32;      // 32-channel blocks of the output
+    constexpr int CPR = DH / 8;      // 16-byte chunks per head row
+    __shared__ AttnSmem<DH> sm;
+    const int d = H * DH;
+    const int b = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * 128;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hl = lane >> 5;
+    const int qw0 = q0 + wave * 32, qi = qw0 + l32;       // this lane's query
+    const size_t base = (size_t)b * N * d + (size_t)h * DH;
+
+    f16x4 qf[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        if (qi < N)
+            qf[t] = *reinterpret_cast<const f16x4 *>(q + base + (size_t)qi * d + 8 * t + 4 * hl);
+        else
+            qf[t] = f16x4{0, 0, 0, 0};
+    }
+    f32x16 oacc[DB];
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[i][r] = 0.0f;
+    float m_run = -INFINITY, l_run = 0.0f;
+
+    const int q_last_wg = min(q0 + 127, N - 1);
+    for (int kt0 = 0; kt0 <= q_last_wg; kt0 += KT) {
+        __syncthreads();
+        // stage K rows (8-byte stores) and V transposed (2-byte stores, lane = key)
+        for (int i = tid; i < KT * CPR; i += 256) {
+            int key = i / CPR, c = i % CPR;
+            Pack16 kk;
+            kk.u = make_uint4(0, 0, 0, 0);
+            if (kt0 + key < N)
+                kk.u = *reinterpret_cast<const uint4 *>(khat + base + (size_t)(kt0 + key) * d + 8 * c);
+            uint2 *dst = reinterpret_cast<uint2 *>(&sm.k[key][8 * c]);
+            dst[0] = make_uint2(kk.w[0], kk.w[1]);
+            dst[1] = make_uint2(kk.w[2], kk.w[3]);
+        }
+        for (int i = tid; i < KT * CPR; i += 256) {
+            int key = i % KT, c = i / KT;
+            Pack16 vv;
+            vv.u = make_uint4(0, 0, 0, 0);
+            if (kt0 + key < N)
+                vv.u = *reinterpret_cast<const uint4 *>(vhat + base + (size_t)(kt0 + key) * d + 8 * c);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sm.vt[8 * c + e][key] = vv.h[e];
+        }
+        __syncthreads();
+        if (kt0 > qw0 + 31) continue;        // tile entirely above this wave's diagonal
+
+        f32x16 s[2];
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[sb][r] = 0.0f;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                f16x4 kf = *reinterpret_cast<const f16x4 *>(&sm.k[32 * sb + l32][8 * t + 4 * hl]);
+                s[sb] = __builtin_amdgcn_mfma_f32_32x32x8f16(kf, qf[t], s[sb], 0, 0, 0);
+            }
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int key = kt0 + 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
+                float v = s[sb][r] * scale_log2;
+                v = (key <= qi && key < N) ? v : -INFINITY;
+                s[sb][r] = v;
+                mx = fmaxf(mx, v);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        float m_new = fmaxf(m_run, mx);
+        float alpha = exp2f(m_run - m_new);
+        m_run = m_new;
+        float psum = 0.0f;
+        f16x4 pf[2][4];
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float p0 = exp2f(s[sb][4 * u + 0] - m_new), p1 = exp2f(s[sb][4 * u + 1] - m_new);
+                float p2 = exp2f(s[sb][4 * u + 2] - m_new), p3 = exp2f(s[sb][4 * u + 3] - m_new);
+                psum += (p0 + p1) + (p2 + p3);
+                pf[sb][u] = f16x4{(f16)p0, (f16)p1, (f16)p2, (f16)p3};
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int i = 0; i < DB; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+#pragma unroll
+            for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    f16x4 vf = *reinterpret_cast<const f16x4 *>(
+                        &sm.vt[32 * i + l32][32 * sb + 8 * u + 4 * hl]);
+                    oacc[i] = __builtin_amdgcn_mfma_f32_32x32x8f16(vf, pf[sb][u], oacc[i], 0, 0, 0);
+                }
+        }
+    }
+    float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    if (qi < N) {
+        float inv = 1.0f / l_tot;
+#pragma unroll
+        for (int i = 0; i < DB; ++i)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f16x4 ov = f16x4{(f16)(oacc[i][4 * g + 0] * inv), (f16)(oacc[i][4 * g + 1] * inv),
+                                 (f16)(oacc[i][4 * g + 2] * inv), (f16)(oacc[i][4 * g + 3] * inv)};
+                *reinterpret_cast<f16x4 *>(o + base + (size_t)qi * d + 32 * i + 8 * g + 4 * hl) = ov;
+            }
+        if (hl == 0) lse2[((size_t)b * H + h) * N + qi] = m_run + log2f(l_tot);
+    }
+}
+
+template <int DH>
+struct CmSmem {
+    f16 q[KT][DH + 4];
+    float lse[KT];
+};
+
+// grid: (ceil(Nv/128), H, B); wave w owns the 32 visual keys kb .. kb+31
+template <int DH>
+__global__ __launch_bounds__(256) void colmass_kernel(
+    const f16 *__restrict__ q, const f16 *__restrict__ khat, const float *__restrict__ lse2, int N,
+    int H, int vis_begin, int Nv, float *__restrict__ partial, float scale_log2)
+{
+    constexpr int T = DH / 8, CPR = DH / 8;
+    __shared__ CmSmem<DH> sm;
+    const int d = H * DH;
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hl = lane >> 5;
+    const int kwg = vis_begin + blockIdx.x * 128;         // first key of the workgroup
+    const int key = kwg + wave * 32 + l32;                // this lane's key column
+    const bool key_ok = key < vis_begin + Nv;
+    const size_t base = (size_t)b * N * d + (size_t)h * DH;
+
+    f16x4 kf[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        if (key_ok)
+            kf[t] = *reinterpret_cast<const f16x4 *>(khat + base + (size_t)key * d + 8 * t + 4 * hl);
+        else
+            kf[t] = f16x4{0, 0, 0, 0};
+    }
+    float acc_txt = 0.0f, acc_vis = 0.0f;
+    for (int qt0 = (kwg / KT) * KT; qt0 < N; qt0 += KT) {
+        __syncthreads();
+        for (int i = tid; i < KT * CPR; i += 256) {
+            int r = i / CPR, c = i % CPR;
+            Pack16 qq;
+            qq.u = make_uint4(0, 0, 0, 0);
+            if (qt0 + r < N)
+                qq.u = *reinterpret_cast<const uint4 *>(q + base + (size_t)(qt0 + r) * d + 8 * c);
+            uint2 *dst = reinterpret_cast<uint2 *>(&sm.q[r][8 * c]);
+            dst[0] = make_uint2(qq.w[0], qq.w[1]);
+            dst[1] = make_uint2(qq.w[2], qq.w[3]);
+        }
+        if (tid < KT) sm.lse[tid] = qt0 + tid < N ? lse2[((size_t)b * H + h) * N + qt0 + tid] : 0.0f;
+        __syncthreads();
+        if (qt0 + KT - 1 < kwg + wave * 32) continue;     // all queries before this wave's keys
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb) {
+            f32x16 s;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] = 0.0f;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                f16x4 qf = *reinterpret_cast<const f16x4 *>(&sm.q[32 * sb + l32][8 * t + 4 * hl]);
+                s = __builtin_amdgcn_mfma_f32_32x32x8f16(qf, kf[t], s, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int ql = 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
+                int qi = qt0 + ql;
+                float p = exp2f(s[r] * scale_log2 - sm.lse[ql]);
+                p = (key_ok && key <= qi && qi < N) ? p : 0.0f;
+                bool vis = qi >= vis_begin && qi < vis_begin + Nv;
+                acc_vis += vis ? p : 0.0f;
+                acc_txt += vis ? 0.0f : p;
+            }
+        }
+    }
+    acc_txt += __shfl_xor(acc_txt, 32, 64);
+    acc_vis += __shfl_xor(acc_vis, 32, 64);
+    if (key_ok && hl == 0) {
+        size_t oidx = (((size_t)b * H + h) * Nv + (key - vis_begin)) * 2;
+        partial[oidx] = acc_txt;
+        partial[oidx + 1] = acc_vis;
+    }
+}
+
+// head mean in head order: cm[b][i] = (1/H) * sum_h partial[b][h][i]
+__global__ __launch_bounds__(256) void colmass_reduce_kernel(
+    const float *__restrict__ partial, int B, int H, int Nv, float *__restrict__ cm_inter,
+    float *__restrict__ cm_intra)
+{
+    int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= B * Nv) return;
+    int b = t / Nv, i = t % Nv;
+    float st = 0.0f, sv = 0.0f;
+    for (int h = 0; h < H; ++h) {
+        size_t idx = (((size_t)b * H + h) * Nv + i) * 2;
+        st += partial[idx];
+        sv += partial[idx + 1];
+    }
+    float invH = 1.0f / (float)H;
+    if (cm_inter) cm_inter[t] = st * invH;
+    if (cm_intra) cm_intra[t] = sv * invH;
+}
+
+}  // namespace
+
+extern "C" size_t quota_attention_workspace_bytes(int B, int N, int H, int dh)
+{
+    (void)dh;
+    if (B <= 0 || N <= 0 || H <= 0) return 0;
+    // row log-sum-exp [B][H][N] + per-head column masses [B][H][N][2]
+    return (size_t)B * H * N * sizeof(float) * 3;
+}
+
+extern "C" int quota_attention_prefill(const void *q_f16, const void *khat_f16,
+                                       const void *vhat_f16, int B, int N, int H, int dh,
+                                       int vis_begin, int Nv, void *o_f16, float *cm_inter,
+                                       float *cm_intra, void *ws, void *stream)
+{
+    if (!q_f16 || !khat_f16 || !vhat_f16 || !o_f16 || !ws) return QUOTA_ERR_NULL;
+    if (B <= 0 || N < 0 || H <= 0 || vis_begin < 0 || Nv < 0 || vis_begin + Nv > N)
+        return QUOTA_ERR_INVALID_ARG;
+    if (dh != 64 && dh != 128) return QUOTA_ERR_SHAPE;
+    if (N == 0) return QUOTA_OK;
+    hipStream_t st = (hipStream_t)stream;
+    float *lse2 = (float *)ws;
+    float *partial = lse2 + (size_t)B * H * N;
+    float scale_log2 = 1.4426950408889634f / sqrtf((float)dh);
+    dim3 g1((N + 127) / 128, H, B), blk(256);
+    const f16 *q = (const f16 *)q_f16, *k = (const f16 *)khat_f16, *v = (const f16 *)vhat_f16;
+    if (dh == 128)
+        attn_fwd_kernel<128><<<g1, blk, 0, st>>>(q, k, v, N, H, (f16 *)o_f16, lse2, scale_log2);
+    else
+        attn_fwd_kernel<64><<<g1, blk, 0, st>>>(q, k, v, N, H, (f16 *)o_f16, lse2, scale_log2);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    if (Nv > 0 && (cm_inter || cm_intra)) {
+        dim3 g2((Nv + 127) / 128, H, B);
+        if (dh == 128)
+            colmass_kernel<128><<<g2, blk, 0, st>>>(q, k, lse2, N, H, vis_begin, Nv, partial, scale_log2);
+        else
+            colmass_kernel<64><<<g2, blk, 0, st>>>(q, k, lse2, N, H, vis_begin, Nv, partial, scale_log2);
+        QUOTA_RETURN_IF_LAUNCH_FAILED();
+        colmass_reduce_kernel<<<dim3((B * Nv + 255) / 256), blk, 0, st>>>(partial, B, H, Nv, cm_inter,
+                                                                          cm_intra);
+        QUOTA_RETURN_IF_LAUNCH_FAILED();
+    }
+    return QUOTA_OK;
+}

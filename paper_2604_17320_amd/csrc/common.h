@@ -1,0 +1,83 @@
+// Shared device helpers for the gfx950 kernels of libquota (wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+#include "../../include/quota.h"
+
+#define QUOTA_WAVE 64
+
+// launch-error check used by every host entry point after it enqueues kernels
+#define QUOTA_RETURN_IF_LAUNCH_FAILED()                    \
+    do {                                                   \
+        if (hipGetLastError() != hipSuccess) return QUOTA_ERR_HIP; \
+    } while (0)
+
+typedef _Float16 f16;
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+
+union Pack16 {           // 16 bytes seen as halves, dwords or one vector load
+    uint4 u;
+    f16 h[8];
+    uint32_t w[4];
+};
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// block-wide (blockDim.x = 64*NW) max of a float and sum of up to two doubles;
+// every thread gets the result.  `sm` needs 3*NW doubles of LDS.
+template <int NW>
+__device__ __forceinline__ void block_max_sum2(float &mx, double &s0, double &s1, double *sm)
+{
+    mx = wave_max(mx);
+    s0 = wave_sum(s0);
+    s1 = wave_sum(s1);
+    int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    __syncthreads();          // protect sm against the previous use
+    if (l == 0) { sm[w] = (double)mx; sm[NW + w] = s0; sm[2 * NW + w] = s1; }
+    __syncthreads();
+    float m = (float)sm[0];
+    double a = sm[NW], b = sm[2 * NW];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) { m = fmaxf(m, (float)sm[i]); a += sm[NW + i]; b += sm[2 * NW + i]; }
+    mx = m; s0 = a; s1 = b;
+}
+
+// fp32 -> fp16 with the fp32 value materialised first.  Without the barrier
+// the compiler may fold "multiply/add, then convert" into one mixed-precision
+// instruction that rounds the exact result straight to fp16; the two-step
+// rounding written here is what the rest of the pipeline is defined with.
+__device__ __forceinline__ f16 to_f16(float v)
+{
+    asm volatile("" : "+v"(v));
+    return (f16)v;
+}
+
+// int4 code from a rounded fp32 value: clamp to [-8, 7]
+__device__ __forceinline__ int code_from(float r)
+{
+    r = fminf(fmaxf(r, -8.0f), 7.0f);
+    return (int)r;
+}

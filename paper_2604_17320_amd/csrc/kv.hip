@@ -1,0 +1,238 @@
+// RoPE + 4-bit K/V quantization, KV-cache append and the compaction gather.
+// All bandwidth-bound: one lane owns 8 consecutive channels (one 16-byte load),
+// the 8 lanes of a 64-channel KV group reduce their absmax with three
+// xor-shuffles and each lane stores one packed dword of 8 codes.
+#include "common.h"
+#include "internal.h"
+
+namespace {
+
+// Quantize this lane's 8 channels; the 8 lanes [lane & ~7, +8) form one group.
+// Returns packed codes; *sh = fp16 group scale; xhat (optional) = code * scale.
+__device__ __forceinline__ uint32_t kv_quant8(const float f[8], f16 *sh_out, Pack16 *xhat)
+{
+    float a = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(f[e]));
+    a = fmaxf(a, __shfl_xor(a, 1, 64));
+    a = fmaxf(a, __shfl_xor(a, 2, 64));
+    a = fmaxf(a, __shfl_xor(a, 4, 64));
+    f16 sh = to_f16(a / 7.0f);
+    float s = (float)sh;
+    if (a == 0.0f || s == 0.0f) { sh = (f16)1.0f; s = 1.0f; }
+    float r = 1.0f / s;
+    uint32_t word = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        int code = code_from(rintf(f[e] * r));
+        word |= (uint32_t)(code & 0xF) << (4 * e);
+        if (xhat) xhat->h[e] = to_f16((float)code * s);
+    }
+    *sh_out = sh;
+    return word;
+}
+
+// thread t -> (row, 8-channel chunk c); q | k | v chunks at the same c
+template <int DH>
+__global__ __launch_bounds__(256) void rope_kv_quant_kernel(
+    const f16 *__restrict__ qkv, int M, int d, const int32_t *__restrict__ pos, int n_pos,
+    const float *__restrict__ cosT, const float *__restrict__ sinT, f16 *__restrict__ q_rot,
+    f16 *__restrict__ khat, f16 *__restrict__ vhat, uint32_t *__restrict__ kc,
+    f16 *__restrict__ ks, uint32_t *__restrict__ vc, f16 *__restrict__ vs)
+{
+    constexpr int CPH = DH / 8, HALF = CPH / 2;     // chunks per head, per half head
+    const int cpr = d >> 3;                          // chunks per row
+    long t = (long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= (long)M * cpr) return;
+    int row = (int)(t / cpr), c = (int)(t % cpr);
+    int cc = c % CPH;
+    bool second = cc >= HALF;
+    const f16 *base = qkv + (size_t)row * 3 * d + 8 * c;
+    Pack16 q, k, v;
+    q.u = *reinterpret_cast<const uint4 *>(base);
+    k.u = *reinterpret_cast<const uint4 *>(base + d);
+    v.u = *reinterpret_cast<const uint4 *>(base + 2 * d);
+    Pack16 qp, kp;                                   // rotate-half partner chunk
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        qp.w[i] = __shfl_xor(q.w[i], HALF, 64);
+        kp.w[i] = __shfl_xor(k.w[i], HALF, 64);
+    }
+    const int pr = min(max(pos[row], 0), n_pos - 1);     // never index outside the tables
+    const float *cp = cosT + (size_t)pr * (DH / 2) + 8 * (cc % HALF);
+    const float *sp = sinT + (size_t)pr * (DH / 2) + 8 * (cc % HALF);
+    float cs[8], sn[8];
+    *reinterpret_cast<float4 *>(cs) = *reinterpret_cast<const float4 *>(cp);
+    *reinterpret_cast<float4 *>(cs + 4) = *reinterpret_cast<const float4 *>(cp + 4);
+    *reinterpret_cast<float4 *>(sn) = *reinterpret_cast<const float4 *>(sp);
+    *reinterpret_cast<float4 *>(sn + 4) = *reinterpret_cast<const float4 *>(sp + 4);
+    Pack16 qo;
+    float kf[8], vf[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float a = (float)q.h[e] * cs[e];
+        float b = (float)qp.h[e] * sn[e];
+        qo.h[e] = to_f16(second ? a + b : a - b);
+        float a2 = (float)k.h[e] * cs[e];
+        float b2 = (float)kp.h[e] * sn[e];
+        kf[e] = (float)to_f16(second ? a2 + b2 : a2 - b2);   // rotated k is an fp16 tensor
+        vf[e] = (float)v.h[e];
+    }
+    *reinterpret_cast<uint4 *>(q_rot + (size_t)row * d + 8 * c) = qo.u;
+    Pack16 kh, vh;
+    f16 ksc, vsc;
+    uint32_t kw = kv_quant8(kf, &ksc, &kh);
+    uint32_t vw = kv_quant8(vf, &vsc, &vh);
+    *reinterpret_cast<uint4 *>(khat + (size_t)row * d + 8 * c) = kh.u;
+    *reinterpret_cast<uint4 *>(vhat + (size_t)row * d + 8 * c) = vh.u;
+    kc[(size_t)row * cpr + c] = kw;
+    vc[(size_t)row * cpr + c] = vw;
+    if ((c & 7) == 0) {
+        ks[(size_t)row * (cpr >> 3) + (c >> 3)] = ksc;
+        vs[(size_t)row * (cpr >> 3) + (c >> 3)] = vsc;
+    }
+}
+
+__global__ __launch_bounds__(256) void kv_quant_append_kernel(
+    const f16 *__restrict__ k, const f16 *__restrict__ v, int B, int N, int d,
+    const int32_t *__restrict__ keep_rows, int n_keep, int capacity, int len,
+    uint32_t *__restrict__ kc, f16 *__restrict__ ks, uint32_t *__restrict__ vc, f16 *__restrict__ vs)
+{
+    const int cpr = d >> 3;
+    long t = (long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= (long)B * n_keep * cpr) return;
+    int c = (int)(t % cpr);
+    long rj = t / cpr;
+    int j = (int)(rj % n_keep), b = (int)(rj / n_keep);
+    int src = keep_rows ? keep_rows[(size_t)b * n_keep + j] : j;
+    src = min(max(src, 0), N - 1);                      // never read outside the sequence
+    size_t srow = (size_t)b * N + src, drow = (size_t)b * capacity + len + j;
+    Pack16 kk, vv;
+    kk.u = *reinterpret_cast<const uint4 *>(k + srow * d + 8 * c);
+    vv.u = *reinterpret_cast<const uint4 *>(v + srow * d + 8 * c);
+    float kf[8], vf[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { kf[e] = (float)kk.h[e]; vf[e] = (float)vv.h[e]; }
+    f16 ksc, vsc;
+    uint32_t kw = kv_quant8(kf, &ksc, nullptr);
+    uint32_t vw = kv_quant8(vf, &vsc, nullptr);
+    kc[drow * cpr + c] = kw;
+    vc[drow * cpr + c] = vw;
+    if ((c & 7) == 0) {
+        ks[drow * (cpr >> 3) + (c >> 3)] = ksc;
+        vs[drow * (cpr >> 3) + (c >> 3)] = vsc;
+    }
+}
+
+// Compaction gather of the layer (one workgroup per kept row): copies the
+// kept rows of the hidden state, the attention output and the positions, and
+// moves their staged 4-bit K/V rows into the layer's cache.
+__global__ __launch_bounds__(256) void compact_rows_kernel(
+    int N, int vis_begin, int Nv, int k_keep, int n_keep, const int32_t *__restrict__ keep_idx,
+    int d, const f16 *__restrict__ x, const f16 *__restrict__ o, const int32_t *__restrict__ pos,
+    const uint32_t *__restrict__ skc, const f16 *__restrict__ sks, const uint32_t *__restrict__ svc,
+    const f16 *__restrict__ svs, f16 *__restrict__ x_out, f16 *__restrict__ o_out,
+    int32_t *__restrict__ pos_out, int32_t *__restrict__ rows_out, int capacity, int len,
+    uint32_t *__restrict__ ckc, f16 *__restrict__ cks, uint32_t *__restrict__ cvc,
+    f16 *__restrict__ cvs)
+{
+    int j = blockIdx.x, b = blockIdx.y;
+    int src;
+    if (j < vis_begin) src = j;
+    else if (j < vis_begin + k_keep) src = vis_begin + keep_idx[(size_t)b * k_keep + (j - vis_begin)];
+    else src = j - k_keep + Nv;
+    src = min(max(src, 0), N - 1);
+    size_t srow = (size_t)b * N + src, drow = (size_t)b * n_keep + j;
+    size_t crow = (size_t)b * capacity + len + j;
+    const int n16 = d >> 3;       // 16-byte pieces in an fp16 row
+    const uint4 *xs = reinterpret_cast<const uint4 *>(x + srow * d);
+    const uint4 *os = reinterpret_cast<const uint4 *>(o + srow * d);
+    uint4 *xd = reinterpret_cast<uint4 *>(x_out + drow * d);
+    uint4 *od = reinterpret_cast<uint4 *>(o_out + drow * d);
+    for (int i = threadIdx.x; i < n16; i += 256) { xd[i] = xs[i]; od[i] = os[i]; }
+    for (int i = threadIdx.x; i < n16; i += 256) {          // d/8 dwords of codes per row
+        ckc[crow * n16 + i] = skc[srow * n16 + i];
+        cvc[crow * n16 + i] = svc[srow * n16 + i];
+    }
+    const int ng = d >> 6;
+    for (int i = threadIdx.x; i < ng; i += 256) {
+        cks[crow * ng + i] = sks[srow * ng + i];
+        cvs[crow * ng + i] = svs[srow * ng + i];
+    }
+    if (threadIdx.x == 0) {
+        pos_out[drow] = pos[srow];
+        if (rows_out) rows_out[drow] = src;
+    }
+}
+
+}  // namespace
+
+int quota_internal_compact(const quota_compact_args *a, hipStream_t st)
+{
+    quota_kv_cache *c = a->cache;
+    if (c->len + a->n_keep > c->capacity) return QUOTA_ERR_CAPACITY;
+    if (a->n_keep == 0) return QUOTA_OK;
+    compact_rows_kernel<<<dim3(a->n_keep, a->B), dim3(256), 0, st>>>(
+        a->N, a->vis_begin, a->Nv, a->k_keep, a->n_keep, a->keep_idx, a->d, (const f16 *)a->x,
+        (const f16 *)a->o, a->pos, (const uint32_t *)a->skc, (const f16 *)a->sks,
+        (const uint32_t *)a->svc, (const f16 *)a->svs, (f16 *)a->x_out, (f16 *)a->o_out, a->pos_out,
+        a->rows_out, c->capacity, c->len, (uint32_t *)c->k_codes, (f16 *)c->k_scales,
+        (uint32_t *)c->v_codes, (f16 *)c->v_scales);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    c->len += a->n_keep;
+    return QUOTA_OK;
+}
+
+extern "C" int quota_rope_kv_quant(const void *qkv_f16, int M, int H, int dh, const int32_t *pos,
+                                   const float *cosT, const float *sinT, int n_pos,
+                                   void *q_rot_f16, void *khat_f16, void *vhat_f16,
+                                   uint8_t *k_codes, void *k_scales, uint8_t *v_codes,
+                                   void *v_scales, void *stream)
+{
+    if (!qkv_f16 || !pos || !cosT || !sinT || !q_rot_f16 || !khat_f16 || !vhat_f16 || !k_codes ||
+        !k_scales || !v_codes || !v_scales)
+        return QUOTA_ERR_NULL;
+    if (M < 0 || H <= 0 || n_pos <= 0) return QUOTA_ERR_INVALID_ARG;
+    if (dh != 64 && dh != 128) return QUOTA_ERR_SHAPE;
+    if (M == 0) return QUOTA_OK;
+    int d = H * dh;
+    long total = (long)M * (d >> 3);
+    dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    hipStream_t st = (hipStream_t)stream;
+    if (dh == 128)
+        rope_kv_quant_kernel<128><<<grid, block, 0, st>>>(
+            (const f16 *)qkv_f16, M, d, pos, n_pos, cosT, sinT, (f16 *)q_rot_f16, (f16 *)khat_f16,
+            (f16 *)vhat_f16, (uint32_t *)k_codes, (f16 *)k_scales, (uint32_t *)v_codes,
+            (f16 *)v_scales);
+    else
+        rope_kv_quant_kernel<64><<<grid, block, 0, st>>>(
+            (const f16 *)qkv_f16, M, d, pos, n_pos, cosT, sinT, (f16 *)q_rot_f16, (f16 *)khat_f16,
+            (f16 *)vhat_f16, (uint32_t *)k_codes, (f16 *)k_scales, (uint32_t *)v_codes,
+            (f16 *)v_scales);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    return QUOTA_OK;
+}
+
+extern "C" int quota_kv_quant_append(const void *k_f16, const void *v_f16, int B, int N, int H,
+                                     int dh, const int32_t *keep_rows, int n_keep,
+                                     quota_kv_cache *cache, void *stream)
+{
+    if (!k_f16 || !v_f16 || !cache || !cache->k_codes || !cache->k_scales || !cache->v_codes ||
+        !cache->v_scales)
+        return QUOTA_ERR_NULL;
+    if (B <= 0 || N < 0 || H <= 0 || n_keep < 0 || cache->len < 0) return QUOTA_ERR_INVALID_ARG;
+    if (dh % 64 != 0 || cache->H != H || cache->dh != dh || cache->B != B) return QUOTA_ERR_SHAPE;
+    if (!keep_rows && n_keep > N) return QUOTA_ERR_INVALID_ARG;
+    if (cache->len + n_keep > cache->capacity) return QUOTA_ERR_CAPACITY;
+    if (n_keep == 0) return QUOTA_OK;
+    int d = H * dh;
+    long total = (long)B * n_keep * (d >> 3);
+    kv_quant_append_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                             (hipStream_t)stream>>>(
+        (const f16 *)k_f16, (const f16 *)v_f16, B, N, d, keep_rows, n_keep, cache->capacity,
+        cache->len, (uint32_t *)cache->k_codes, (f16 *)cache->k_scales,
+        (uint32_t *)cache->v_codes, (f16 *)cache->v_scales);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    cache->len += n_keep;
+    return QUOTA_OK;
+}

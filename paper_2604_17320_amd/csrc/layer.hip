@@ -1,0 +1,183 @@
+// quota_prefill_layer: host-side sequencing of one W4A4 decoder layer with
+// in-layer visual-token pruning.  No device allocation, no synchronisation:
+// every intermediate lives in the caller's workspace and every step is a
+// kernel enqueued on the caller's stream (safe to capture in a HIP graph).
+#include "common.h"
+#include "internal.h"
+
+namespace {
+
+struct Carver {
+    char *base;
+    size_t off;
+    template <typename T>
+    T *take(size_t count)
+    {
+        size_t bytes = (count * sizeof(T) + 255) & ~(size_t)255;
+        T *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+        off += bytes;
+        return p;
+    }
+};
+
+struct LayerWs {
+    uint8_t *qa;        // packed int4 activations of the current GEMM input
+    float *sa;
+    f16 *qkv, *q_rot, *khat, *vhat, *o;
+    uint8_t *skc, *svc; // staged 4-bit K/V of all rows
+    f16 *sks, *svs;
+    float *sumsq, *ressq, *cm_inter, *cm_intra, *score;
+    int32_t *keep_idx, *rows;
+    f16 *x_keep, *o_keep, *x1, *gu;
+    void *attn_ws;
+    size_t bytes;
+};
+
+LayerWs carve(void *ws, int B, int N, int H, int dh, int F)
+{
+    Carver c{(char *)ws, 0};
+    LayerWs w;
+    size_t M = (size_t)B * N, d = (size_t)H * dh;
+    size_t kmax = d > (size_t)F ? d : (size_t)F;
+    w.qa = c.take<uint8_t>(M * kmax / 2);
+    w.sa = c.take<float>(M);
+    w.qkv = c.take<f16>(M * 3 * d);
+    w.q_rot = c.take<f16>(M * d);
+    w.khat = c.take<f16>(M * d);
+    w.vhat = c.take<f16>(M * d);
+    w.o = c.take<f16>(M * d);
+    w.skc = c.take<uint8_t>(M * d / 2);
+    w.svc = c.take<uint8_t>(M * d / 2);
+    w.sks = c.take<f16>(M * d / 64);
+    w.svs = c.take<f16>(M * d / 64);
+    w.sumsq = c.take<float>(M);
+    w.ressq = c.take<float>(M);
+    w.cm_inter = c.take<float>(M);
+    w.cm_intra = c.take<float>(M);
+    w.score = c.take<float>(M);
+    w.keep_idx = c.take<int32_t>(M);
+    w.rows = c.take<int32_t>(M);
+    w.x_keep = c.take<f16>(M * d);
+    w.o_keep = c.take<f16>(M * d);
+    w.x1 = c.take<f16>(M * d);
+    w.gu = c.take<f16>(M * 2 * (size_t)F);
+    w.attn_ws = c.take<char>(quota_attention_workspace_bytes(B, N, H, dh));
+    w.bytes = c.off;
+    return w;
+}
+
+__global__ void copy_f32_kernel(const float *__restrict__ src, float *__restrict__ dst, long n,
+                                int seg, long src_stride, long src_off)
+{
+    // dst[b*seg + i] = src[b*src_stride + src_off + i]
+    long t = (long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= n) return;
+    long b = t / seg, i = t % seg;
+    dst[t] = src[b * src_stride + src_off + i];
+}
+
+int dump(void *dst, const void *src, size_t bytes, hipStream_t st)
+{
+    if (!dst || bytes == 0) return QUOTA_OK;
+    return hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, st) == hipSuccess ? QUOTA_OK
+                                                                                       : QUOTA_ERR_HIP;
+}
+
+}  // namespace
+
+#define TRY(expr)                         \
+    do {                                  \
+        int rc_ = (expr);                 \
+        if (rc_ != QUOTA_OK) return rc_;  \
+    } while (0)
+
+extern "C" size_t quota_prefill_workspace_bytes(const quota_layer *L, int B, int N)
+{
+    if (!L || B <= 0 || N <= 0 || L->H <= 0 || L->dh <= 0 || L->F <= 0) return 0;
+    return carve(nullptr, B, N, L->H, L->dh, L->F).bytes;
+}
+
+extern "C" int quota_prefill_layer(const quota_layer *L, quota_state *s, int K_l,
+                                   const quota_score_params *p, quota_kv_cache *cache,
+                                   const quota_taps *taps, void *ws, void *stream)
+{
+    if (!L || !s || !p || !cache || !ws || !s->x || !s->pos || !s->x_out || !s->pos_out ||
+        !L->gamma1 || !L->gamma2 || !L->cosT || !L->sinT)
+        return QUOTA_ERR_NULL;
+    const int B = s->B, N = s->N, vb = s->vis_begin, Nv = s->Nv, H = L->H, dh = L->dh, F = L->F;
+    if (B <= 0 || N <= 0 || vb < 0 || Nv < 0 || vb + Nv > N || K_l < 0) return QUOTA_ERR_INVALID_ARG;
+    const int d = H * dh;
+    if ((dh != 64 && dh != 128) || F % 32 != 0) return QUOTA_ERR_SHAPE;
+    if (L->qkv.N != 3 * d || L->qkv.K != d || L->o.N != d || L->o.K != d || L->gu.N != 2 * F ||
+        L->gu.K != d || L->down.N != d || L->down.K != F)
+        return QUOTA_ERR_SHAPE;
+    if (cache->B != B || cache->H != H || cache->dh != dh) return QUOTA_ERR_SHAPE;
+    const int k_keep = K_l < Nv ? K_l : Nv;
+    const int n_keep = N - Nv + k_keep;
+    if (cache->len + n_keep > cache->capacity) return QUOTA_ERR_CAPACITY;
+
+    hipStream_t st = (hipStream_t)stream;
+    LayerWs w = carve(ws, B, N, H, dh, F);
+    const int M = B * N, Mk = B * n_keep;
+    static const quota_taps no_taps = {};
+    const quota_taps *t = taps ? taps : &no_taps;
+
+    // attention half on every token that entered the layer
+    TRY(quota_rmsnorm_quantize_act(s->x, M, d, d, L->gamma1, L->eps, w.qa, w.sa, w.sumsq, w.ressq,
+                                   nullptr, st));
+    TRY(quota_w4a4_gemm(w.qa, w.sa, M, &L->qkv, w.qkv, 3 * d, nullptr, 0, nullptr, st));
+    TRY(dump(t->qkv, w.qkv, (size_t)M * 3 * d * 2, st));
+    TRY(quota_rope_kv_quant(w.qkv, M, H, dh, s->pos, L->cosT, L->sinT, L->n_pos, w.q_rot, w.khat,
+                            w.vhat, w.skc, w.sks, w.svc, w.svs, st));
+    TRY(dump(t->q_rot, w.q_rot, (size_t)M * d * 2, st));
+    TRY(quota_attention_prefill(w.q_rot, w.khat, w.vhat, B, N, H, dh, vb, Nv, w.o, w.cm_inter,
+                                w.cm_intra, w.attn_ws, st));
+    TRY(dump(t->o, w.o, (size_t)M * d * 2, st));
+    const f16 *o_used = t->inject_o ? (const f16 *)t->inject_o : w.o;
+    const float *cmi = t->inject_cm_inter ? t->inject_cm_inter : w.cm_inter;
+    const float *cmv = t->inject_cm_intra ? t->inject_cm_intra : w.cm_intra;
+
+    // Eq. 6-9: cues -> G -> fused score -> top-K_l over the visual tokens
+    if (Nv > 0) {
+        TRY(quota_internal_score(w.sumsq + vb, w.ressq + vb, N, cmi, cmv, B, Nv, p, w.score, nullptr,
+                                 st));
+        if (k_keep > 0) TRY(quota_topk_prune(w.score, B, Nv, k_keep, w.keep_idx, st));
+        if (t->sumsq || t->ressq) {
+            long n = (long)B * Nv;
+            dim3 g((unsigned)((n + 255) / 256)), blk(256);
+            if (t->sumsq) copy_f32_kernel<<<g, blk, 0, st>>>(w.sumsq, t->sumsq, n, Nv, N, vb);
+            if (t->ressq) copy_f32_kernel<<<g, blk, 0, st>>>(w.ressq, t->ressq, n, Nv, N, vb);
+            QUOTA_RETURN_IF_LAUNCH_FAILED();
+        }
+        TRY(dump(t->cm_inter, w.cm_inter, (size_t)B * Nv * 4, st));
+        TRY(dump(t->cm_intra, w.cm_intra, (size_t)B * Nv * 4, st));
+        TRY(dump(t->score, w.score, (size_t)B * Nv * 4, st));
+        TRY(dump(t->keep_idx, w.keep_idx, (size_t)B * k_keep * 4, st));
+    }
+
+    // compaction: kept rows of x / o / pos move on, their 4-bit K/V go to the cache
+    quota_compact_args ca;
+    ca.B = B; ca.N = N; ca.vis_begin = vb; ca.Nv = Nv; ca.k_keep = k_keep; ca.n_keep = n_keep;
+    ca.d = d; ca.keep_idx = w.keep_idx; ca.x = s->x; ca.o = o_used; ca.pos = s->pos;
+    ca.skc = w.skc; ca.sks = w.sks; ca.svc = w.svc; ca.svs = w.svs;
+    ca.x_out = w.x_keep; ca.o_out = w.o_keep; ca.pos_out = s->pos_out; ca.rows_out = w.rows;
+    ca.cache = cache;
+    TRY(quota_internal_compact(&ca, st));
+    TRY(dump(t->rows, w.rows, (size_t)Mk * 4, st));
+
+    // token-wise rest of the block on the kept rows only
+    if (Mk > 0) {
+        TRY(quota_quantize_act(w.o_keep, Mk, d, d, w.qa, w.sa, nullptr, nullptr, st));
+        TRY(quota_w4a4_gemm(w.qa, w.sa, Mk, &L->o, w.x1, d, w.x_keep, d, nullptr, st));
+        TRY(dump(t->x1, w.x1, (size_t)Mk * d * 2, st));
+        TRY(quota_rmsnorm_quantize_act(w.x1, Mk, d, d, L->gamma2, L->eps, w.qa, w.sa, nullptr,
+                                       nullptr, nullptr, st));
+        TRY(quota_w4a4_gemm(w.qa, w.sa, Mk, &L->gu, w.gu, 2 * F, nullptr, 0, nullptr, st));
+        TRY(dump(t->gu, w.gu, (size_t)Mk * 2 * F * 2, st));
+        TRY(quota_silu_mul_quantize_act(w.gu, Mk, F, w.qa, w.sa, t->z, t->inject_z, st));
+        TRY(quota_w4a4_gemm(w.qa, w.sa, Mk, &L->down, s->x_out, d, w.x1, d, nullptr, st));
+    }
+    s->N = n_keep;
+    s->Nv = k_keep;
+    return QUOTA_OK;
+}

@@ -1,0 +1,361 @@
+// Quantizers of the W4A4 execution form: weight group quantizer + repack,
+// per-token int4 activation quantizer (the Q of Eq. 6) and its fused variants
+// (RMSNorm in front of QKV / gate-up, SwiGLU product in front of down).
+// All are row kernels: one 256-thread workgroup per row, the row cached in
+// registers as 16-byte chunks, block reductions for absmax / sums of squares,
+// one packed dword (8 codes) stored per chunk.  HBM-bound by design.
+#include "common.h"
+#include "internal.h"
+
+// ------------------------------------------------------------ W4 weights
+
+// one wave per (row n, group g): 2 elements per lane
+__global__ __launch_bounds__(256) void quantize_weights_kernel(
+    const float *__restrict__ w, int N, int K, int G, int8_t *__restrict__ codes,
+    f16 *__restrict__ scales)
+{
+    long wave = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    int lane = threadIdx.x & 63;
+    if (wave >= (long)N * G) return;
+    int n = (int)(wave / G), g = (int)(wave % G);
+    int k = g * QUOTA_GROUP_W + 2 * lane;
+    const float *wr = w + (size_t)n * K;
+    float v0 = k < K ? wr[k] : 0.0f;
+    float v1 = k + 1 < K ? wr[k + 1] : 0.0f;
+    float a = wave_max(fmaxf(fabsf(v0), fabsf(v1)));
+    f16 sh = to_f16(a / 7.0f);
+    float s = (float)sh;
+    if (a == 0.0f || s == 0.0f) { sh = (f16)1.0f; s = 1.0f; }
+    if (lane == 0) scales[(size_t)n * G + g] = sh;
+    if (k < K) codes[(size_t)n * K + k] = (int8_t)code_from(rintf(v0 / s));
+    if (k + 1 < K) codes[(size_t)n * K + k + 1] = (int8_t)code_from(rintf(v1 / s));
+}
+
+// codes int8 [N][K] -> packed [G][N][16 dwords]; scales [N][G] -> [G][N]
+__global__ __launch_bounds__(256) void pack_weights_kernel(
+    const int8_t *__restrict__ codes, const f16 *__restrict__ scales, int N, int K, int G,
+    uint32_t *__restrict__ packed, f16 *__restrict__ scales_t)
+{
+    long t = (long)blockIdx.x * 256 + threadIdx.x;
+    long total = (long)G * N * 16;
+    if (t >= total) return;
+    int i = (int)(t & 15);
+    long gn = t >> 4;
+    int n = (int)(gn % N), g = (int)(gn / N);
+    int k0 = g * QUOTA_GROUP_W + 8 * i;
+    uint32_t word = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        int k = k0 + e;
+        int c = k < K ? (int)codes[(size_t)n * K + k] : 0;
+        word |= (uint32_t)(c & 0xF) << (4 * e);
+    }
+    packed[t] = word;
+    if (i == 0) scales_t[(size_t)g * N + n] = scales[(size_t)n * G + g];
+}
+
+// ------------------------------------------------- activation quantizers
+
+#define ROW_THREADS 256
+#define ROW_MAXCHUNK 8   // 8 chunks * 8 halves * 256 threads = 16384 columns
+
+// final phase shared by the three row kernels: quantize the cached row `v`
+// with absmax `a`, store packed codes, return this thread's residual sum.
+template <bool WANT_RES>
+__device__ __forceinline__ double quantize_cached_row(const Pack16 *v, int nchunk, float a,
+                                                      uint32_t *__restrict__ qrow, float &s_out)
+{
+    float s = 1.0f, inv = 0.0f;
+    if (a != 0.0f) { s = a / 7.0f; inv = 7.0f / a; }
+    s_out = s;
+    double rs = 0.0;
+#pragma unroll
+    for (int r = 0; r < ROW_MAXCHUNK; ++r) {
+        int c = threadIdx.x + ROW_THREADS * r;
+        if (c < nchunk) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float f = (float)v[r].h[e];
+                int code = code_from(rintf(f * inv));
+                word |= (uint32_t)(code & 0xF) << (4 * e);
+                if (WANT_RES) {
+                    float deq = (float)code * s;
+                    float rr = deq - f;
+                    rs += (double)rr * (double)rr;
+                }
+            }
+            if (qrow) qrow[c] = word;
+        }
+    }
+    return rs;
+}
+
+template <bool WANT_METRICS>
+__global__ __launch_bounds__(ROW_THREADS) void quantize_act_kernel(
+    const f16 *__restrict__ x, int d, long ldx, int rows_per_seq, long seq_stride,
+    uint32_t *__restrict__ q, float *__restrict__ scale, float *__restrict__ sumsq,
+    float *__restrict__ ressq)
+{
+    __shared__ double sm[12];
+    int row = blockIdx.x, nchunk = d >> 3;
+    const uint4 *xr = reinterpret_cast<const uint4 *>(
+        x + (size_t)(row / rows_per_seq) * seq_stride + (size_t)(row % rows_per_seq) * ldx);
+    Pack16 v[ROW_MAXCHUNK];
+    float a = 0.0f;
+    double ss = 0.0, zero = 0.0;
+#pragma unroll
+    for (int r = 0; r < ROW_MAXCHUNK; ++r) {
+        int c = threadIdx.x + ROW_THREADS * r;
+        if (c < nchunk) {
+            v[r].u = xr[c];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float f = (float)v[r].h[e];
+                a = fmaxf(a, fabsf(f));
+                if (WANT_METRICS) ss += (double)f * (double)f;
+            }
+        }
+    }
+    block_max_sum2<4>(a, ss, zero, sm);
+    float s;
+    double rs = quantize_cached_row<WANT_METRICS>(v, nchunk, a, q ? q + (size_t)row * nchunk : nullptr, s);
+    if (WANT_METRICS) {
+        float dummy = 0.0f;
+        block_max_sum2<4>(dummy, rs, zero, sm);
+    }
+    if (threadIdx.x == 0) {
+        if (scale) scale[row] = s;
+        if (WANT_METRICS) {
+            if (sumsq) sumsq[row] = (float)ss;
+            if (ressq) ressq[row] = (float)rs;
+        }
+    }
+}
+
+template <bool WANT_METRICS>
+__global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
+    const f16 *__restrict__ x, int d, long ldx, const float *__restrict__ gamma, float eps,
+    uint32_t *__restrict__ q, float *__restrict__ scale, float *__restrict__ sumsq,
+    float *__restrict__ ressq, f16 *__restrict__ h_out)
+{
+    __shared__ double sm[12];
+    int row = blockIdx.x, nchunk = d >> 3;
+    const uint4 *xr = reinterpret_cast<const uint4 *>(x + (size_t)row * ldx);
+    Pack16 v[ROW_MAXCHUNK];
+    float a_raw = 0.0f;
+    double ss = 0.0, zero = 0.0;
+#pragma unroll
+    for (int r = 0; r < ROW_MAXCHUNK; ++r) {
+        int c = threadIdx.x + ROW_THREADS * r;
+        if (c < nchunk) {
+            v[r].u = xr[c];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float f = (float)v[r].h[e];
+                a_raw = fmaxf(a_raw, fabsf(f));
+                ss += (double)f * (double)f;
+            }
+        }
+    }
+    block_max_sum2<4>(a_raw, ss, zero, sm);
+    float rn = (float)(1.0 / sqrt(ss / (double)d + (double)eps));
+    float s_raw = 1.0f, inv_raw = 0.0f;
+    if (a_raw != 0.0f) { s_raw = a_raw / 7.0f; inv_raw = 7.0f / a_raw; }
+    float a = 0.0f;
+    double rs = 0.0;
+#pragma unroll
+    for (int r = 0; r < ROW_MAXCHUNK; ++r) {
+        int c = threadIdx.x + ROW_THREADS * r;
+        if (c < nchunk) {
+            const float4 *gp = reinterpret_cast<const float4 *>(gamma + 8 * c);
+            float4 g0 = gp[0], g1 = gp[1];
+            float gm[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float f = (float)v[r].h[e];
+                if (WANT_METRICS) {
+                    int code = code_from(rintf(f * inv_raw));
+                    float deq = (float)code * s_raw;
+                    float rr = deq - f;
+                    rs += (double)rr * (double)rr;
+                }
+                float hn = f * rn;
+                hn = hn * gm[e];
+                f16 hh = to_f16(hn);
+                v[r].h[e] = hh;
+                a = fmaxf(a, fabsf((float)hh));
+            }
+            if (h_out) reinterpret_cast<uint4 *>(h_out + (size_t)row * d)[c] = v[r].u;
+        }
+    }
+    block_max_sum2<4>(a, rs, zero, sm);
+    float s;
+    quantize_cached_row<false>(v, nchunk, a, q + (size_t)row * nchunk, s);
+    if (threadIdx.x == 0) {
+        scale[row] = s;
+        if (WANT_METRICS) {
+            if (sumsq) sumsq[row] = (float)ss;
+            if (ressq) ressq[row] = (float)rs;
+        }
+    }
+}
+
+__global__ __launch_bounds__(ROW_THREADS) void silu_mul_quantize_act_kernel(
+    const f16 *__restrict__ gu, int F, uint32_t *__restrict__ q, float *__restrict__ scale,
+    f16 *__restrict__ z_out, const f16 *__restrict__ z_inject)
+{
+    __shared__ double sm[12];
+    int row = blockIdx.x, nchunk = F >> 3;
+    const uint4 *gr = reinterpret_cast<const uint4 *>(gu + (size_t)row * 2 * F);
+    const uint4 *ur = reinterpret_cast<const uint4 *>(gu + (size_t)row * 2 * F + F);
+    Pack16 v[ROW_MAXCHUNK];
+    float a = 0.0f;
+    double z0 = 0.0, z1 = 0.0;
+#pragma unroll
+    for (int r = 0; r < ROW_MAXCHUNK; ++r) {
+        int c = threadIdx.x + ROW_THREADS * r;
+        if (c < nchunk) {
+            if (z_inject) {
+                v[r].u = reinterpret_cast<const uint4 *>(z_inject + (size_t)row * F)[c];
+            } else {
+                Pack16 g, u;
+                g.u = gr[c];
+                u.u = ur[c];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    float gt = (float)g.h[e], up = (float)u.h[e];
+                    float sg = gt / (1.0f + expf(-gt));
+                    v[r].h[e] = to_f16(sg * up);
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf((float)v[r].h[e]));
+            if (z_out) reinterpret_cast<uint4 *>(z_out + (size_t)row * F)[c] = v[r].u;
+        }
+    }
+    block_max_sum2<4>(a, z0, z1, sm);
+    float s;
+    quantize_cached_row<false>(v, nchunk, a, q + (size_t)row * nchunk, s);
+    if (threadIdx.x == 0) scale[row] = s;
+}
+
+// ------------------------------------------------------------ host side
+
+extern "C" size_t quota_weights_packed_bytes(int N, int K)
+{
+    if (N <= 0 || K <= 0) return 0;
+    size_t G = ((size_t)K + QUOTA_GROUP_W - 1) / QUOTA_GROUP_W;
+    return G * (size_t)N * 64;
+}
+
+extern "C" size_t quota_weights_scale_bytes(int N, int K)
+{
+    if (N <= 0 || K <= 0) return 0;
+    size_t G = ((size_t)K + QUOTA_GROUP_W - 1) / QUOTA_GROUP_W;
+    return G * (size_t)N * 2;
+}
+
+extern "C" int quota_quantize_weights(const float *w, int N, int K, int8_t *codes,
+                                      void *scales_f16, void *stream)
+{
+    if (!w || !codes || !scales_f16) return QUOTA_ERR_NULL;
+    if (N <= 0 || K <= 0) return QUOTA_ERR_INVALID_ARG;
+    int G = (K + QUOTA_GROUP_W - 1) / QUOTA_GROUP_W;
+    long waves = (long)N * G;
+    quantize_weights_kernel<<<dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, (hipStream_t)stream>>>(
+        w, N, K, G, codes, (f16 *)scales_f16);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    return QUOTA_OK;
+}
+
+extern "C" int quota_pack_weights(const int8_t *codes, const void *scales_f16,
+                                  const quota_weights *W, void *stream)
+{
+    if (!codes || !scales_f16 || !W || !W->packed || !W->scales) return QUOTA_ERR_NULL;
+    if (W->N <= 0 || W->K <= 0) return QUOTA_ERR_INVALID_ARG;
+    if (W->N % 64 != 0 || W->K % 32 != 0) return QUOTA_ERR_SHAPE;
+    int G = (W->K + QUOTA_GROUP_W - 1) / QUOTA_GROUP_W;
+    long total = (long)G * W->N * 16;
+    pack_weights_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
+        codes, (const f16 *)scales_f16, W->N, W->K, G, (uint32_t *)W->packed, (f16 *)W->scales);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    return QUOTA_OK;
+}
+
+static int check_rows(const void *x, int M, int d, int ld, const void *q, const void *scale)
+{
+    if (!x || !q || !scale) return QUOTA_ERR_NULL;
+    if (M < 0 || d <= 0) return QUOTA_ERR_INVALID_ARG;
+    if (d % 8 != 0 || d > 8 * ROW_THREADS * ROW_MAXCHUNK || ld < d || ld % 8 != 0) return QUOTA_ERR_SHAPE;
+    return QUOTA_OK;
+}
+
+extern "C" int quota_quantize_act(const void *x_f16, int M, int d, int ldx, uint8_t *q_packed,
+                                  float *scale, float *sumsq_opt, float *ressq_opt, void *stream)
+{
+    int rc = check_rows(x_f16, M, d, ldx, q_packed, scale);
+    if (rc != QUOTA_OK) return rc;
+    if (M == 0) return QUOTA_OK;
+    hipStream_t st = (hipStream_t)stream;
+    if (sumsq_opt || ressq_opt)
+        quantize_act_kernel<true><<<dim3(M), dim3(ROW_THREADS), 0, st>>>(
+            (const f16 *)x_f16, d, ldx, M, 0, (uint32_t *)q_packed, scale, sumsq_opt, ressq_opt);
+    else
+        quantize_act_kernel<false><<<dim3(M), dim3(ROW_THREADS), 0, st>>>(
+            (const f16 *)x_f16, d, ldx, M, 0, (uint32_t *)q_packed, scale, nullptr, nullptr);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    return QUOTA_OK;
+}
+
+extern "C" int quota_rmsnorm_quantize_act(const void *x_f16, int M, int d, int ldx,
+                                          const float *gamma, float eps, uint8_t *q_packed,
+                                          float *scale, float *sumsq_opt, float *ressq_opt,
+                                          void *h_opt, void *stream)
+{
+    int rc = check_rows(x_f16, M, d, ldx, q_packed, scale);
+    if (rc != QUOTA_OK) return rc;
+    if (!gamma) return QUOTA_ERR_NULL;
+    if (!(eps >= 0.0f)) return QUOTA_ERR_INVALID_ARG;
+    if (M == 0) return QUOTA_OK;
+    hipStream_t st = (hipStream_t)stream;
+    if (sumsq_opt || ressq_opt)
+        rmsnorm_quantize_act_kernel<true><<<dim3(M), dim3(ROW_THREADS), 0, st>>>(
+            (const f16 *)x_f16, d, ldx, gamma, eps, (uint32_t *)q_packed, scale, sumsq_opt,
+            ressq_opt, (f16 *)h_opt);
+    else
+        rmsnorm_quantize_act_kernel<false><<<dim3(M), dim3(ROW_THREADS), 0, st>>>(
+            (const f16 *)x_f16, d, ldx, gamma, eps, (uint32_t *)q_packed, scale, nullptr, nullptr,
+            (f16 *)h_opt);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    return QUOTA_OK;
+}
+
+extern "C" int quota_silu_mul_quantize_act(const void *gu_f16, int M, int F, uint8_t *q_packed,
+                                           float *scale, void *z_opt, const void *z_inject_opt,
+                                           void *stream)
+{
+    int rc = check_rows(gu_f16, M, F, F, q_packed, scale);
+    if (rc != QUOTA_OK) return rc;
+    if (M == 0) return QUOTA_OK;
+    silu_mul_quantize_act_kernel<<<dim3(M), dim3(ROW_THREADS), 0, (hipStream_t)stream>>>(
+        (const f16 *)gu_f16, F, (uint32_t *)q_packed, scale, (f16 *)z_opt, (const f16 *)z_inject_opt);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    return QUOTA_OK;
+}
+
+// Eq. 6 vector metrics only (no codes stored): sumsq/ressq [B][Nv] of the
+// visual rows v[b][i] = v + b*stride_b + i*ldv.
+int quota_internal_vector_metrics(const void *v_f16, int B, int Nv, int d, int ldv, long stride_b,
+                                  float *sumsq, float *ressq, hipStream_t st)
+{
+    if (!v_f16 || !sumsq || !ressq) return QUOTA_ERR_NULL;
+    if (B <= 0 || Nv < 0 || d <= 0) return QUOTA_ERR_INVALID_ARG;
+    if (d % 8 != 0 || d > 8 * ROW_THREADS * ROW_MAXCHUNK || ldv < d || ldv % 8 != 0 || stride_b % 8 != 0)
+        return QUOTA_ERR_SHAPE;
+    if (Nv == 0) return QUOTA_OK;
+    quantize_act_kernel<true><<<dim3(B * Nv), dim3(ROW_THREADS), 0, st>>>(
+        (const f16 *)v_f16, d, ldv, Nv, stride_b, nullptr, nullptr, sumsq, ressq);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    return QUOTA_OK;
+}
