@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the QUOTA hot path on one MI355X.
+
+One "step" = one prefill pass of the whole layer stack (every kernel of the
+path, all layers) over one batch of seeded synthetic input.  Prints ONE JSON
+line: prefill tokens/s, the roofline figure of the dominant kernel, per-kernel
+timings, and the CPU oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3|c2|c1]
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA, TOP/s
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, GB/s
+
+
+def build_stack(shape, seed, budgets, keep_plain_layers=()):
+    import torch
+    from paper_2604_17320_amd import workloads as wl
+    from paper_2604_17320_amd.model import PackedLinear, PrefillLayer, PrefillStack
+    d, F = shape.d, shape.F
+    cos, sin = wl.rope_tables(shape.dh, shape.N)
+    cosT, sinT = torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda()
+    gamma = torch.ones(d, dtype=torch.float32, device="cuda")
+    layers = []
+    for l in range(shape.layers):
+        g = torch.Generator(device="cuda")
+        g.manual_seed(seed * 1000 + l)
+        lin = {}
+        for name, (n, k) in dict(qkv=(3 * d, d), o=(d, d), gu=(2 * F, d), down=(d, F)).items():
+            w = torch.randn((n, k), generator=g, device="cuda", dtype=torch.float32) * 0.02
+            lin[name] = PackedLinear.from_fp32(w, keep_plain=l in keep_plain_layers)
+            del w
+        layers.append(PrefillLayer(shape.H, shape.dh, F, lin["qkv"], lin["o"], lin["gu"], lin["down"],
+                                   gamma, gamma, 1e-5, cosT, sinT))
+    torch.cuda.synchronize()
+    stack = PrefillStack(layers, shape.B, shape.N, shape.vis_begin, shape.Nv, budgets)
+    return stack, (cos, sin)
+
+
+def cpu_baseline(shape, stack, budgets, rope, sample_layers, seed):
+    """The oracle, as it stands, on a bounded sample: a few layers of the stack, each fed a
+    synthetic hidden state with the row count that layer sees in the real run."""
+    import numpy as np
+    import oracle
+    from paper_2604_17320_amd import workloads as wl
+    cos, sin = rope
+    rows_in = []
+    n, nv = shape.N, shape.Nv
+    for K in budgets:
+        rows_in.append((n, nv))
+        k = min(K, nv)
+        n, nv = n - nv + k, k
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    t_sum, r_sum = 0.0, 0
+    for l in sample_layers:
+        L = stack.layers[l]
+        W = oracle.LayerWeights(
+            **{name: (getattr(L, name).codes.cpu().numpy(), getattr(L, name).plain_scales.cpu().numpy())
+               for name in ("qkv", "o", "gu", "down")},
+            gamma1=np.ones(shape.d, np.float32), gamma2=np.ones(shape.d, np.float32), eps=1e-5,
+            H=shape.H, dh=shape.dh, F=shape.F)
+        n, nv = rows_in[l]
+        sh = wl.Shape("sample", shape.d, shape.H, shape.F, 1, shape.B, nv, n - nv, shape.n_outlier)
+        x = wl.hidden_state(sh, seed + l)
+        pos = wl.positions(sh)
+        t0 = time.perf_counter()
+        oracle.prefill_layer(W, x, pos, shape.B, n, 0, nv, budgets[l], cos, sin, prune_mid=True)
+        t_sum += time.perf_counter() - t0
+        r_sum += shape.B * n
+    rows_total = sum(shape.B * n for n, _ in rows_in)
+    est = t_sum * rows_total / r_sum                 # seconds for the whole stack, by row count
+    return dict(value=shape.B * shape.N / est, unit="tokens/s", cores=threads, kind="oracle",
+                sample=f"layers {list(sample_layers)} of {shape.layers} run in full ({t_sum:.2f} s, {r_sum} "
+                       f"token-rows), scaled by token-rows to all layers ({rows_total} rows)")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--profile-steps", type=int, default=3)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on ONE GPU (no sharding, no collectives); --gpus N>1 is not "
+              "supported. Batch parallelism would need no exchange step; see DESIGN.md.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2604_17320_amd import binding as qb, workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    qb.lib()                                         # fails loudly if libquota.so is missing
+
+    shape = {"c1": wl.CONFIGS[0], "c2": wl.CONFIGS[1], "c3": wl.CONFIGS[2]}[args.config]
+    budgets = wl.schedule_for(shape)
+    sample_layers = sorted({0, min(2, shape.layers - 1), shape.layers // 2, shape.layers - 1})
+    stack, rope = build_stack(shape, args.seed, budgets, keep_plain_layers=() if args.no_cpu else sample_layers)
+    x0 = torch.from_numpy(wl.hidden_state(shape, args.seed)).cuda()
+    pos0 = torch.from_numpy(wl.positions(shape)).cuda()
+
+    def step():
+        return stack.run(x0, pos0)
+
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+
+    graph = None
+    if not args.no_graph:
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step()
+            graph.replay()
+            torch.cuda.synchronize()
+        except Exception as e:                       # noqa: BLE001 -- report and time eagerly instead
+            print(f"bench.py: HIP graph capture failed ({e}); timing eager launches", file=sys.stderr)
+            graph = None
+    run = graph.replay if graph is not None else step
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    tokens = shape.B * shape.N
+    value = tokens * args.steps / elapsed
+
+    # eager timing for reference (launch overhead visible)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(max(1, args.steps // 5)):
+        step()
+    torch.cuda.synchronize()
+    eager_ms = (time.perf_counter() - t0) * 1e3 / max(1, args.steps // 5)
+
+    # per-kernel HIP-event timing over full eager steps
+    kernels_per_step = 20 * shape.layers
+    qb.quota_profile_begin(kernels_per_step * args.profile_steps + 16)
+    for _ in range(args.profile_steps):
+        step()
+    stats = qb.quota_profile_collect()
+    kern = {}
+    for name, s in stats.items():
+        us = s["total_ms"] * 1e3 / s["launches"]
+        kern[name] = dict(launches_per_step=s["launches"] // args.profile_steps, avg_us=round(us, 2),
+                          step_ms=round(s["total_ms"] / args.profile_steps, 4),
+                          GBps=round(s["bytes"] / (s["total_ms"] * 1e-3) / 1e9, 1) if s["total_ms"] else None,
+                          TOPs=round(s["ops"] / (s["total_ms"] * 1e-3) / 1e12, 1) if s["ops"] else None)
+    dom = max(stats, key=lambda k: stats[k]["total_ms"])
+    ds = stats[dom]
+    if ds["ops"] and dom.startswith("w4a4_gemm"):
+        achieved = ds["ops"] / (ds["total_ms"] * 1e-3) / 1e12
+        roofline = dict(kernel=dom, bound="mfma", achieved=round(achieved, 1), peak=PEAK_INT8_TOPS,
+                        unit="TOP/s", frac=round(achieved / PEAK_INT8_TOPS, 4), traffic=None,
+                        avg_launch_us=round(ds["total_ms"] * 1e3 / ds["launches"], 2),
+                        launches_per_step=ds["launches"] // args.profile_steps)
+    else:
+        achieved = ds["bytes"] / (ds["total_ms"] * 1e-3) / 1e9
+        roofline = dict(kernel=dom, bound="hbm", achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                        frac=round(achieved / PEAK_HBM_GBS, 4), traffic=None,
+                        avg_launch_us=round(ds["total_ms"] * 1e3 / ds["launches"], 2),
+                        launches_per_step=ds["launches"] // args.profile_steps)
+    gemm_ops = sum(s["ops"] for n, s in stats.items() if n.startswith("w4a4_gemm"))
+    gemm_ms = sum(s["total_ms"] for n, s in stats.items() if n.startswith("w4a4_gemm"))
+
+    out = dict(metric="prefill_tokens_per_s", value=round(value, 1), unit="tokens/s", n_gpus=1,
+               steps=args.steps, warmup=args.warmup, ms_per_step=round(ms_per_step, 4),
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="int8",
+               data="synthetic",
+               config=dict(workload=f"{shape.name}: {shape.layers}-layer 7B-shaped W4A4 pruned prefill "
+                                    f"(d={shape.d}, H={shape.H}, F={shape.F}), batch {shape.B}, "
+                                    f"{shape.Nv} visual + {shape.Nt} text tokens, per-layer budgets "
+                                    f"{budgets[0]}..{budgets[-1]} (mean keep "
+                                    f"{sum(budgets) / len(budgets) / max(shape.Nv, 1):.3f}), 4-bit KV",
+                           batch=shape.B, tokens_per_step=tokens, layers=shape.layers, seed=args.seed,
+                           hip_graph=graph is not None),
+               eager_ms_per_step=round(eager_ms, 4),
+               roofline=roofline,
+               gemm_all=dict(TOPs=round(gemm_ops / (gemm_ms * 1e-3) / 1e12, 1) if gemm_ms else None,
+                             frac_int8_peak=round(gemm_ops / (gemm_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 4)
+                             if gemm_ms else None, step_ms=round(gemm_ms / args.profile_steps, 4)),
+               kernels=kern)
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(shape, stack, budgets, rope, sample_layers, args.seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

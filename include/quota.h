@@ -287,6 +287,41 @@ int quota_prefill_layer(const quota_layer *L, quota_state *st, int K_l,
                         const quota_score_params *p, quota_kv_cache *cache,
                         const quota_taps *taps_opt, void *ws, void *stream);
 
+/* ---- per-kernel timing for benchmarks ----------------------------------- */
+
+/* Kernel classes the library launches.  The GEMM is split by tile shape
+ * because each shape is a separate kernel (and a separate profiler row). */
+enum {
+    QUOTA_K_QUANTIZE_ACT = 0, QUOTA_K_RMSNORM_QUANTIZE_ACT, QUOTA_K_SILU_MUL_QUANTIZE_ACT,
+    QUOTA_K_GEMM_128X128, QUOTA_K_GEMM_64X64, QUOTA_K_GEMM_OTHER, QUOTA_K_ROPE_KV_QUANT,
+    QUOTA_K_KV_QUANT_APPEND, QUOTA_K_ATTENTION_FWD, QUOTA_K_ATTENTION_COLMASS,
+    QUOTA_K_SCORE_TOKENS, QUOTA_K_TOPK_PRUNE, QUOTA_K_COMPACT_ROWS, QUOTA_K_QUANTIZE_WEIGHTS,
+    QUOTA_K_PACK_WEIGHTS, QUOTA_KERNEL_COUNT
+};
+
+/* Per kernel class: launches seen, summed HIP-event time around them (ms) and
+ * the ALGORITHMIC work those launches stood for: integer/float operations
+ * (2 per multiply-add) and bytes the operation must move (inputs read once +
+ * outputs written once, int4 data counted as half bytes). */
+typedef struct quota_kernel_stat {
+    long launches;
+    double total_ms;
+    double ops;
+    double bytes;
+} quota_kernel_stat;
+
+const char *quota_kernel_name(int kernel_id);
+
+/* Starts recording a HIP-event pair around every kernel launch the library
+ * makes (on the launch's own stream), for at most max_launches launches; more
+ * are not recorded.  Allocates host memory and HIP events: not for the hot
+ * path, and recording must not be active during HIP graph capture. */
+int quota_profile_begin(int max_launches);
+
+/* Stops recording, waits for the recorded events, fills
+ * stats[QUOTA_KERNEL_COUNT] (host) and frees the events. */
+int quota_profile_collect(quota_kernel_stat *stats);
+
 #ifdef __cplusplus
 }
 #endif

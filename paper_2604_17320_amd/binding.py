@@ -58,6 +58,12 @@ class Taps(C.Structure):
                  "rows", "x1", "gu", "z", "inject_o", "inject_cm_inter", "inject_cm_intra", "inject_z"]]
 
 
+class KernelStat(C.Structure):
+    _fields_ = [("launches", C.c_long), ("total_ms", C.c_double), ("ops", C.c_double), ("bytes", C.c_double)]
+
+
+KERNEL_COUNT = 15
+
 _lib = None
 
 
@@ -70,6 +76,7 @@ def lib() -> C.CDLL:
                                "(there is no fallback path)")
         L = C.CDLL(LIB_PATH)
         L.quota_strerror.restype = C.c_char_p
+        L.quota_kernel_name.restype = C.c_char_p
         for name in ["quota_weights_packed_bytes", "quota_weights_scale_bytes",
                      "quota_attention_workspace_bytes", "quota_prefill_workspace_bytes"]:
             getattr(L, name).restype = C.c_size_t
@@ -206,3 +213,19 @@ def quota_prefill_layer(L: Layer, st: State, K_l, p: ScoreParams, cache: KVCache
     _check(lib().quota_prefill_layer(C.byref(L), C.byref(st), int(K_l), C.byref(p), C.byref(cache),
                                      C.byref(taps) if taps is not None else None, _ptr(ws), _stream()),
            "quota_prefill_layer")
+
+
+def quota_profile_begin(max_launches: int):
+    _check(lib().quota_profile_begin(int(max_launches)), "quota_profile_begin")
+
+
+def quota_profile_collect():
+    """Returns {kernel name: dict(launches, total_ms, ops, bytes)} for the kernels that ran."""
+    arr = (KernelStat * KERNEL_COUNT)()
+    _check(lib().quota_profile_collect(arr), "quota_profile_collect")
+    out = {}
+    for i in range(KERNEL_COUNT):
+        if arr[i].launches:
+            out[lib().quota_kernel_name(i).decode()] = dict(launches=arr[i].launches, total_ms=arr[i].total_ms,
+                                                            ops=arr[i].ops, bytes=arr[i].bytes)
+    return out

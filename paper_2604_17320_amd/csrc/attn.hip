@@ -268,13 +268,20 @@ extern "C" int quota_attention_prefill(const void *q_f16, const void *khat_f16,
     float scale_log2 = 1.4426950408889634f / sqrtf((float)dh);
     dim3 g1((N + 127) / 128, H, B), blk(256);
     const f16 *q = (const f16 *)q_f16, *k = (const f16 *)khat_f16, *v = (const f16 *)vhat_f16;
-    if (dh == 128)
-        attn_fwd_kernel<128><<<g1, blk, 0, st>>>(q, k, v, N, H, (f16 *)o_f16, lse2, scale_log2);
-    else
-        attn_fwd_kernel<64><<<g1, blk, 0, st>>>(q, k, v, N, H, (f16 *)o_f16, lse2, scale_log2);
+    const double dM = (double)B * N, dd = (double)H * dh;
+    {
+        ProfScope prof(QUOTA_K_ATTENTION_FWD, 4.0 * B * dd * ((double)N * (N + 1) / 2), 8.0 * dM * dd, st);
+        if (dh == 128)
+            attn_fwd_kernel<128><<<g1, blk, 0, st>>>(q, k, v, N, H, (f16 *)o_f16, lse2, scale_log2);
+        else
+            attn_fwd_kernel<64><<<g1, blk, 0, st>>>(q, k, v, N, H, (f16 *)o_f16, lse2, scale_log2);
+    }
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     if (Nv > 0 && (cm_inter || cm_intra)) {
         dim3 g2((Nv + 127) / 128, H, B);
+        // (query, visual key) pairs under the causal mask
+        const double pairs = (double)Nv * (N - vis_begin) - (double)Nv * (Nv - 1) / 2;
+        ProfScope prof(QUOTA_K_ATTENTION_COLMASS, 2.0 * B * dd * pairs, 4.0 * dM * dd, st);
         if (dh == 128)
             colmass_kernel<128><<<g2, blk, 0, st>>>(q, k, lse2, N, H, vis_begin, Nv, partial, scale_log2);
         else

@@ -4,6 +4,7 @@
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 #include "../../include/quota.h"
+#include "profile.h"
 
 #define QUOTA_WAVE 64
 

@@ -190,11 +190,18 @@ int launch(const uint8_t *qa, const float *sa, int M, const quota_weights *W, f1
     int tiles_m = (M + BM - 1) / BM, tiles_n = (W->N + BN - 1) / BN;
     size_t smem = sizeof(GemmSmem<BM, BN>);
     auto kern = w4a4_gemm_kernel<BM, BN, ACC_OUT>;
-    if (smem > 48 * 1024) {
+    static bool attr_set = false;      // once per tile shape; not a stream operation
+    if (smem > 48 * 1024 && !attr_set) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)smem) != hipSuccess)
             return QUOTA_ERR_HIP;
+        attr_set = true;
     }
+    const double Md = M, Nd = W->N, Kd = W->K;
+    ProfScope prof(BM == 128 && BN == 128 ? QUOTA_K_GEMM_128X128
+                   : (BM == 64 && BN == 64 ? QUOTA_K_GEMM_64X64 : QUOTA_K_GEMM_OTHER),
+                   2.0 * Md * Nd * Kd,
+                   Nd * Kd / 2 + 2.0 * Nd * G + Md * Kd / 2 + 4 * Md + 2.0 * Md * Nd * (res ? 2 : 1), st);
     kern<<<dim3(tiles_m * tiles_n), dim3(256), smem, st>>>(
         qa, sa, M, W->K, G, (const uint4 *)W->packed, (const f16 *)W->scales, W->N, y, ldy, res,
         ldr, acc, tiles_m, tiles_n);

@@ -172,6 +172,8 @@ int quota_internal_compact(const quota_compact_args *a, hipStream_t st)
     quota_kv_cache *c = a->cache;
     if (c->len + a->n_keep > c->capacity) return QUOTA_ERR_CAPACITY;
     if (a->n_keep == 0) return QUOTA_OK;
+    const double rows = (double)a->n_keep * a->B, dd = a->d;
+    ProfScope prof(QUOTA_K_COMPACT_ROWS, 0, rows * (2 * (4 * dd + dd + dd / 16) + 8), st);
     compact_rows_kernel<<<dim3(a->n_keep, a->B), dim3(256), 0, st>>>(
         a->N, a->vis_begin, a->Nv, a->k_keep, a->n_keep, a->keep_idx, a->d, (const f16 *)a->x,
         (const f16 *)a->o, a->pos, (const uint32_t *)a->skc, (const f16 *)a->sks,
@@ -199,6 +201,7 @@ extern "C" int quota_rope_kv_quant(const void *qkv_f16, int M, int H, int dh, co
     long total = (long)M * (d >> 3);
     dim3 grid((unsigned)((total + 255) / 256)), block(256);
     hipStream_t st = (hipStream_t)stream;
+    ProfScope prof(QUOTA_K_ROPE_KV_QUANT, 0, (double)M * d * (6 + 6 + 1 + 1.0 / 16) + 4.0 * M, st);
     if (dh == 128)
         rope_kv_quant_kernel<128><<<grid, block, 0, st>>>(
             (const f16 *)qkv_f16, M, d, pos, n_pos, cosT, sinT, (f16 *)q_rot_f16, (f16 *)khat_f16,
@@ -227,6 +230,8 @@ extern "C" int quota_kv_quant_append(const void *k_f16, const void *v_f16, int B
     if (n_keep == 0) return QUOTA_OK;
     int d = H * dh;
     long total = (long)B * n_keep * (d >> 3);
+    ProfScope prof(QUOTA_K_KV_QUANT_APPEND, 0, (double)B * n_keep * d * (4 + 1 + 1.0 / 16),
+                   (hipStream_t)stream);
     kv_quant_append_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
                              (hipStream_t)stream>>>(
         (const f16 *)k_f16, (const f16 *)v_f16, B, N, d, keep_rows, n_keep, cache->capacity,

@@ -263,6 +263,7 @@ extern "C" int quota_quantize_weights(const float *w, int N, int K, int8_t *code
     if (N <= 0 || K <= 0) return QUOTA_ERR_INVALID_ARG;
     int G = (K + QUOTA_GROUP_W - 1) / QUOTA_GROUP_W;
     long waves = (long)N * G;
+    ProfScope prof(QUOTA_K_QUANTIZE_WEIGHTS, 0, 5.0 * N * K + 2.0 * N * G, (hipStream_t)stream);
     quantize_weights_kernel<<<dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, (hipStream_t)stream>>>(
         w, N, K, G, codes, (f16 *)scales_f16);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
@@ -277,6 +278,7 @@ extern "C" int quota_pack_weights(const int8_t *codes, const void *scales_f16,
     if (W->N % 64 != 0 || W->K % 32 != 0) return QUOTA_ERR_SHAPE;
     int G = (W->K + QUOTA_GROUP_W - 1) / QUOTA_GROUP_W;
     long total = (long)G * W->N * 16;
+    ProfScope prof(QUOTA_K_PACK_WEIGHTS, 0, 1.5 * W->N * W->K + 4.0 * W->N * G, (hipStream_t)stream);
     pack_weights_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
         codes, (const f16 *)scales_f16, W->N, W->K, G, (uint32_t *)W->packed, (f16 *)W->scales);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
@@ -298,6 +300,7 @@ extern "C" int quota_quantize_act(const void *x_f16, int M, int d, int ldx, uint
     if (rc != QUOTA_OK) return rc;
     if (M == 0) return QUOTA_OK;
     hipStream_t st = (hipStream_t)stream;
+    ProfScope prof(QUOTA_K_QUANTIZE_ACT, 0, 2.5 * M * d + 4.0 * M, st);
     if (sumsq_opt || ressq_opt)
         quantize_act_kernel<true><<<dim3(M), dim3(ROW_THREADS), 0, st>>>(
             (const f16 *)x_f16, d, ldx, M, 0, (uint32_t *)q_packed, scale, sumsq_opt, ressq_opt);
@@ -319,6 +322,7 @@ extern "C" int quota_rmsnorm_quantize_act(const void *x_f16, int M, int d, int l
     if (!(eps >= 0.0f)) return QUOTA_ERR_INVALID_ARG;
     if (M == 0) return QUOTA_OK;
     hipStream_t st = (hipStream_t)stream;
+    ProfScope prof(QUOTA_K_RMSNORM_QUANTIZE_ACT, 0, 2.5 * M * d + 4.0 * M + 4.0 * d, st);
     if (sumsq_opt || ressq_opt)
         rmsnorm_quantize_act_kernel<true><<<dim3(M), dim3(ROW_THREADS), 0, st>>>(
             (const f16 *)x_f16, d, ldx, gamma, eps, (uint32_t *)q_packed, scale, sumsq_opt,
@@ -338,6 +342,7 @@ extern "C" int quota_silu_mul_quantize_act(const void *gu_f16, int M, int F, uin
     int rc = check_rows(gu_f16, M, F, F, q_packed, scale);
     if (rc != QUOTA_OK) return rc;
     if (M == 0) return QUOTA_OK;
+    ProfScope prof(QUOTA_K_SILU_MUL_QUANTIZE_ACT, 0, 4.5 * M * F + 4.0 * M, (hipStream_t)stream);
     silu_mul_quantize_act_kernel<<<dim3(M), dim3(ROW_THREADS), 0, (hipStream_t)stream>>>(
         (const f16 *)gu_f16, F, (uint32_t *)q_packed, scale, (f16 *)z_opt, (const f16 *)z_inject_opt);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
@@ -354,6 +359,7 @@ int quota_internal_vector_metrics(const void *v_f16, int B, int Nv, int d, int l
     if (d % 8 != 0 || d > 8 * ROW_THREADS * ROW_MAXCHUNK || ldv < d || ldv % 8 != 0 || stride_b % 8 != 0)
         return QUOTA_ERR_SHAPE;
     if (Nv == 0) return QUOTA_OK;
+    ProfScope prof(QUOTA_K_QUANTIZE_ACT, 0, 2.0 * B * Nv * d + 8.0 * B * Nv, st);
     quantize_act_kernel<true><<<dim3(B * Nv), dim3(ROW_THREADS), 0, st>>>(
         (const f16 *)v_f16, d, ldv, Nv, stride_b, nullptr, nullptr, sumsq, ressq);
     QUOTA_RETURN_IF_LAUNCH_FAILED();

@@ -211,6 +211,7 @@ int quota_internal_score(const float *sumsq, const float *ressq, long stride_sq,
         return QUOTA_ERR_INVALID_ARG;
     if (Nv > MAXV) return QUOTA_ERR_SHAPE;
     if (Nv == 0) return QUOTA_OK;
+    ProfScope prof(QUOTA_K_SCORE_TOKENS, 0, 20.0 * B * Nv, st);
     score_kernel<<<dim3(B), dim3(256), 0, st>>>(sumsq, ressq, stride_sq, cm_inter, cm_intra, B, Nv,
                                                 *p, score, normed);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
@@ -241,6 +242,7 @@ extern "C" int quota_topk_prune(const float *score, int B, int Nv, int K, int32_
     if (Nv > MAXV) return QUOTA_ERR_SHAPE;
     int k = K < Nv ? K : Nv;
     if (k == 0) return QUOTA_OK;
+    ProfScope prof(QUOTA_K_TOPK_PRUNE, 0, 4.0 * B * Nv + 4.0 * B * k, (hipStream_t)stream);
     topk_kernel<<<dim3(B), dim3(256), 0, (hipStream_t)stream>>>(score, Nv, k, keep_idx);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
