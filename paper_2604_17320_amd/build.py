@@ -14,6 +14,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",                       # every fp32 step rounds; fma only where written
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",     # MFMA results in VGPRs: the epilogue reads them directly
     "-Wall", "-Wno-unused-function",
 ]
 

@@ -1,6 +1,6 @@
-// W4A4 GEMM for gfx950: int4 codes (activations and weights) are unpacked to
-// int8 on the way into LDS and contracted with v_mfma_i32_32x32x32_i8; the
-// per-group weight scales are applied in fp32 inside the K loop.
+// W4A4 GEMM for gfx950: int4 codes are unpacked to int8 and contracted with
+// v_mfma_i32_32x32x32_i8; the per-group weight scales are applied in fp32
+// inside the K loop (one convert + one fma per output element and group).
 //
 // Unpack trick: a nibble placed in the HIGH half of a byte is the int8 value
 // 16*code (two's complement carries the sign), so "(w << 4) & 0xF0F0F0F0" and
@@ -9,20 +9,22 @@
 // accumulator is therefore exactly 256x the true integer dot product; the
 // factor 2^-8 is folded into the token scale (exact in fp32).
 //
-// The order of k inside a 128-wide group does not matter for an integer dot
-// product, so both operands simply use the same unpack and the same LDS chunk
-// order: chunk 2c holds the even elements of packed 16-byte chunk c, chunk
-// 2c+1 the odd ones.
+// Data flow per 128-deep group:
+//   activations: global (packed) -> registers -> unpack -> LDS (int8, shared by
+//                the 4 waves) -> MFMA A fragments
+//   weights:     global (packed) -> registers -> unpack -> MFMA B fragments.
+//                The 4 waves of a workgroup own disjoint column ranges, so a
+//                weight is needed by exactly one wave and never touches LDS.
+// The order of k inside a group does not matter for an integer dot product,
+// so both operands just use the same assignment of elements to MFMA k-slots:
+// a 16-byte packed chunk c (32 codes) yields "even" (low nibbles) and "odd"
+// (high nibbles) int8 vectors; lane half h of k-step ks takes the even (ks
+// even) or odd (ks odd) vector of chunk 2*h + ks/2.
 #include "common.h"
 
 namespace {
 
-template <int BM, int BN>
-struct GemmSmem {
-    // [stage][row][128 bytes], 16-byte chunks XOR-swizzled by (row & 7)
-    uint4 a[2][BM * 8];
-    uint4 b[2][BN * 8];
-};
+constexpr int AROW = 9;     // LDS row stride in 16-byte units: 8 data + 1 pad (conflict-free b128)
 
 __device__ __forceinline__ void unpack16(const uint4 &v, uint4 &lo, uint4 &hi)
 {
@@ -30,6 +32,10 @@ __device__ __forceinline__ void unpack16(const uint4 &v, uint4 &lo, uint4 &hi)
     lo.y = (v.y << 4) & 0xF0F0F0F0u; hi.y = v.y & 0xF0F0F0F0u;
     lo.z = (v.z << 4) & 0xF0F0F0F0u; hi.z = v.z & 0xF0F0F0F0u;
     lo.w = (v.w << 4) & 0xF0F0F0F0u; hi.w = v.w & 0xF0F0F0F0u;
+}
+__device__ __forceinline__ i32x4 as_i32x4(const uint4 &t)
+{
+    return i32x4{(int)t.x, (int)t.y, (int)t.z, (int)t.w};
 }
 
 // XCD-aware tile id: consecutive dispatch ids go round-robin over the 8 XCDs
@@ -41,60 +47,85 @@ __device__ __forceinline__ int xcd_remap(int pid, int total)
     return x * per + (x < rem ? x : rem) + idx;
 }
 
-template <int BM, int BN, bool ACC_OUT>
+// Workgroup tile (32*TM) x (128*TN); wave w owns columns [w*32*TN, (w+1)*32*TN).
+template <int TM, int TN, int DEPTH, bool ACC_OUT>
 __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
     const uint8_t *__restrict__ qa, const float *__restrict__ sa, int M, int K, int G,
     const uint4 *__restrict__ wp, const f16 *__restrict__ sw, int N, f16 *__restrict__ y, int ldy,
-    const f16 *__restrict__ res, int ldr, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n)
+    const f16 *__restrict__ res, int ldr, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n,
+    int vec_store)
 {
-    constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
-    constexpr int LA = BM * 4 / 256, LB = BN * 4 / 256;   // 16-byte loads per thread per group
-    static_assert(LA >= 1 && LB >= 1, "tile too small for 256 threads");
-    extern __shared__ uint4 smem_raw[];
-    GemmSmem<BM, BN> &sm = *reinterpret_cast<GemmSmem<BM, BN> *>(smem_raw);
+    constexpr int BM = 32 * TM, WN = 32 * TN, BN = 4 * WN;
+    constexpr int LA = (BM * 4 + 255) / 256;         // 16-byte activation loads per thread per group
+    constexpr int CROW = WN + 8;                     // halves per staged output row (16-byte pad)
+    constexpr int LDS_A = 2 * BM * AROW, LDS_C = 4 * 32 * CROW / 8;     // in uint4
+    __shared__ uint4 lds_raw[LDS_A > LDS_C ? LDS_A : LDS_C];
+    uint4 (*lds_a)[BM * AROW] = reinterpret_cast<uint4 (*)[BM * AROW]>(lds_raw);
 
     const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
     const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, hl = lane >> 5;
-    const int Kb = K >> 1;   // bytes per activation row
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hl = lane >> 5;
+    const int Kb = K >> 1;   // bytes per packed activation row
 
-    uint4 ra[LA], rb[LB];
-    auto load_group = [&](int g) {
+    // Global loads are unconditional with clamped addresses (no branches in the
+    // main loop): rows past M or N repeat the last row and are never stored; a
+    // chunk past the end of a ragged K repeats the last chunk and meets the
+    // zero padding of the packed weights.  Addresses are a wave-uniform base
+    // that advances with the group plus a loop-invariant 32-bit lane offset.
+    unsigned oa[LA];                // byte offset of this thread's activation chunk in group 0
+    int ca[LA], la[LA];
+    bool a_on[LA];
+#pragma unroll
+    for (int j = 0; j < LA; ++j) {
+        int i = tid + 256 * j, row = i >> 2, c = i & 3;
+        a_on[j] = row < BM;
+        row = min(row, BM - 1);
+        ca[j] = c * 16;
+        oa[j] = (unsigned)(min(m0 + row, M - 1) - m0) * (unsigned)Kb;
+        la[j] = row * AROW + 2 * c;
+    }
+    const uint8_t *abase = qa + (size_t)m0 * Kb;
+    unsigned ow[TN], os[TN];        // uint4 / f16 index of this lane's weight chunk / scale in group 0
+    int ncol[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        ncol[j] = n0 + wave * WN + 32 * j + l32;
+        int n = min(ncol[j], N - 1);
+        ow[j] = (unsigned)n * 4 + 2 * hl;
+        os[j] = (unsigned)n;
+    }
+
+    uint4 ra[DEPTH][LA], rw[DEPTH][TN][2];
+    f16 rs[DEPTH][TN];
+    auto load_group = [&](int stage, int g) {
+        g = min(g, G - 1);
+        const uint4 *wg = wp + (size_t)g * N * 4;        // uniform
+        const f16 *sg = sw + (size_t)g * N;              // uniform
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            rw[stage][j][0] = wg[ow[j]];
+            rw[stage][j][1] = wg[ow[j] + 1];
+            rs[stage][j] = sg[os[j]];
+        }
 #pragma unroll
         for (int j = 0; j < LA; ++j) {
-            int i = tid + 256 * j, row = i >> 2, c = i & 3;
-            int m = m0 + row, kb = g * 64 + c * 16;
-            ra[j] = (m < M && kb < Kb)
-                        ? *reinterpret_cast<const uint4 *>(qa + (size_t)m * Kb + kb)
-                        : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int j = 0; j < LB; ++j) {
-            int i = tid + 256 * j, row = i >> 2, c = i & 3;
-            int n = n0 + row;
-            rb[j] = n < N ? wp[((size_t)g * N + n) * 4 + c] : make_uint4(0, 0, 0, 0);
+            int kb = min(g * 64 + ca[j], Kb - 16);
+            ra[stage][j] = *reinterpret_cast<const uint4 *>(abase + oa[j] + (unsigned)kb);
         }
     };
-    auto store_group = [&](int st) {
+    auto store_a = [&](int stage, int st) {
 #pragma unroll
         for (int j = 0; j < LA; ++j) {
-            int i = tid + 256 * j, row = i >> 2, c = i & 3;
             uint4 lo, hi;
-            unpack16(ra[j], lo, hi);
-            sm.a[st][row * 8 + ((2 * c) ^ (row & 7))] = lo;
-            sm.a[st][row * 8 + ((2 * c + 1) ^ (row & 7))] = hi;
-        }
-#pragma unroll
-        for (int j = 0; j < LB; ++j) {
-            int i = tid + 256 * j, row = i >> 2, c = i & 3;
-            uint4 lo, hi;
-            unpack16(rb[j], lo, hi);
-            sm.b[st][row * 8 + ((2 * c) ^ (row & 7))] = lo;
-            sm.b[st][row * 8 + ((2 * c + 1) ^ (row & 7))] = hi;
+            unpack16(ra[stage][j], lo, hi);
+            if (LA * 256 == BM * 4 || a_on[j]) {
+                lds_a[st][la[j]] = lo;
+                lds_a[st][la[j] + 1] = hi;
+            }
         }
     };
 
+    constexpr int T = TM * TN;
     float yacc[TM][TN][16];
     int tot[ACC_OUT ? TM : 1][ACC_OUT ? TN : 1][16];
 #pragma unroll
@@ -106,105 +137,135 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
                 yacc[i][j][r] = 0.0f;
                 if (ACC_OUT) tot[i][j][r] = 0;
             }
+    const int fra = l32 * AROW + 4 * hl;       // this lane's A fragment (row l32 of a 32-row block)
 
-    // this lane's output column in each 32-wide column block, and its scale
-    int ncol[TN];
-    float swn[TN];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) ncol[j] = n0 + wn * WN + 32 * j + l32;
-    auto load_scales = [&](int g) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-            swn[j] = ncol[j] < N ? (float)sw[(size_t)g * N + ncol[j]] : 0.0f;
-    };
-
-    load_group(0);
-    store_group(0);
+    for (int s = 0; s < DEPTH; ++s) load_group(s, s);
+    store_a(0, 0);
     __syncthreads();
 
-    for (int g = 0; g < G; ++g) {
-        const int st = g & 1;
-        if (g + 1 < G) load_group(g + 1);
-        load_scales(g);
-
-        i32x4 fa[TM][4], fb[TN][4];
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            int ch = 2 * ks + hl;
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                int row = wm * WM + 32 * i + l32;
-                uint4 t = sm.a[st][row * 8 + (ch ^ (row & 7))];
-                fa[i][ks] = i32x4{(int)t.x, (int)t.y, (int)t.z, (int)t.w};
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                int row = wn * WN + 32 * j + l32;
-                uint4 t = sm.b[st][row * 8 + (ch ^ (row & 7))];
-                fb[j][ks] = i32x4{(int)t.x, (int)t.y, (int)t.z, (int)t.w};
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i][ks], fb[j][ks], acc, 0, 0, 0);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    yacc[i][j][r] = __builtin_fmaf((float)acc[r], swn[j], yacc[i][j][r]);
-                    if (ACC_OUT) tot[i][j][r] += acc[r];
-                }
-            }
-        if (g + 1 < G) store_group(st ^ 1);
-        __syncthreads();
-    }
-
-    // epilogue: token scale (with the 2^-8 of the shifted operands), residual, fp16
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
+    // Software pipeline over the 32x32 sub-tiles, carried across groups: while the
+    // matrix core runs the 4 MFMAs of a sub-tile, the vector ALU applies the group
+    // scale (one convert + one fma per element) to the previous sub-tile -- for the
+    // first sub-tile of a group that is the last sub-tile of the group before.
+    i32x16 pend = i32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};   // sub-tile awaiting its scale
+    float sw_prev = 0.0f;           // scale that goes with the pending sub-tile
+    bool live_prev = false;
+    auto scale_in = [&](int t, const i32x16 &a, float scale, bool live) {
+        const int i = t / TN, j = t % TN;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            int m = m0 + wm * WM + 32 * i + 8 * (r >> 2) + 4 * hl + (r & 3);
-            if (m >= M) continue;
-            float sam = sa[m] * 0.00390625f;
+            yacc[i][j][r] = __builtin_fmaf((float)a[r], scale, yacc[i][j][r]);
+            if (ACC_OUT) tot[i][j][r] += live ? a[r] : 0;
+        }
+    };
+
+    const int Gpad = (G + DEPTH - 1) / DEPTH * DEPTH;
+#pragma unroll 1
+    for (int g0 = 0; g0 < Gpad; g0 += DEPTH) {
+#pragma unroll
+        for (int s = 0; s < DEPTH; ++s) {
+            const int g = g0 + s, st = g & 1;
+            // activation fragments of group g from LDS (latency hidden by the unpack below)
+            i32x4 fa[TM][4];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) fa[i][ks] = as_i32x4(lds_a[st][fra + 32 * i * AROW + ks]);
+            // weights of group g: registers -> int8 B fragments
+            float swn[TN];
+            i32x4 fb[TN][4];
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                int n = ncol[j];
-                if (n >= N) continue;
+                swn[j] = (g < G && ncol[j] < N) ? (float)rs[s][j] : 0.0f;
+                uint4 lo, hi;
+                unpack16(rw[s][j][0], lo, hi);
+                fb[j][0] = as_i32x4(lo);
+                fb[j][1] = as_i32x4(hi);
+                unpack16(rw[s][j][1], lo, hi);
+                fb[j][2] = as_i32x4(lo);
+                fb[j][3] = as_i32x4(hi);
+            }
+            // the stage that held group g is free again: prefetch group g + DEPTH into it
+            // (its activation registers were stored to LDS one iteration ago)
+            load_group(s, g + DEPTH);
+
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const int i = t / TN, j = t % TN;
+                i32x16 a = i32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    a = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i][ks], fb[j][ks], a, 0, 0, 0);
+                if (t == 0) scale_in(T - 1, pend, sw_prev, live_prev);
+                else scale_in(t - 1, pend, swn[(t - 1) % TN], g < G);
+                pend = a;
+            }
+            sw_prev = swn[(T - 1) % TN];
+            live_prev = g < G;
+            store_a((s + 1) % DEPTH, st ^ 1);   // activations of group g+1 -> the other LDS buffer
+            // issue order: fragment reads, weight unpack, prefetch, then 1 MFMA : 8 VALU
+#pragma unroll
+            for (int q = 0; q < 4 * T; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, ACC_OUT ? 12 : 8, 0);
+            }
+            __syncthreads();
+        }
+    }
+    scale_in(T - 1, pend, sw_prev, live_prev);
+
+    // epilogue: token scale (with the 2^-8 of the shifted operands), residual, fp16.
+    // With an aligned output the fp16 tile goes through LDS (the activation buffers
+    // are free after the last barrier) so that every lane stores 16 contiguous bytes.
+    f16 *cw = reinterpret_cast<f16 *>(lds_raw) + wave * 32 * CROW;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = 8 * (r >> 2) + 4 * hl + (r & 3);
+            const int m = m0 + 32 * i + row;
+            const bool m_ok = m < M;
+            const float sam = sa[m_ok ? m : M - 1] * 0.00390625f;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = ncol[j];
+                const bool ok = m_ok && n < N;
                 float v = yacc[i][j][r] * sam;
-                if (res) v = v + (float)res[(size_t)m * ldr + n];
-                if (y) y[(size_t)m * ldy + n] = to_f16(v);
-                if (ACC_OUT) acc_out[(size_t)m * N + n] = tot[i][j][r] >> 8;
+                if (res && ok) v = v + (float)res[(size_t)m * ldr + n];
+                const f16 h = to_f16(v);
+                if (vec_store) cw[row * CROW + 32 * j + l32] = h;
+                else if (y && ok) y[(size_t)m * ldy + n] = h;
+                if (ACC_OUT && ok) acc_out[(size_t)m * N + n] = tot[i][j][r] >> 8;
             }
         }
+        if (vec_store) {
+            __syncthreads();                      // staged tile visible (also fences the type-punned LDS accesses)
+#pragma unroll
+            for (int q = 0; q < 32 * (WN / 8) / 64; ++q) {
+                const int idx = q * 64 + lane, row = idx / (WN / 8), ch = idx % (WN / 8);
+                const int m = m0 + 32 * i + row, n = n0 + wave * WN + 8 * ch;
+                const uint4 v = *reinterpret_cast<const uint4 *>(cw + row * CROW + 8 * ch);
+                if (m < M && n < N) *reinterpret_cast<uint4 *>(y + (size_t)m * ldy + n) = v;
+            }
+            __syncthreads();
+        }
+    }
 }
 
-template <int BM, int BN, bool ACC_OUT>
-int launch(const uint8_t *qa, const float *sa, int M, const quota_weights *W, f16 *y, int ldy,
-           const f16 *res, int ldr, int32_t *acc, hipStream_t st)
+template <int TM, int TN, int DEPTH, bool ACC_OUT>
+int launch(int kernel_id, const uint8_t *qa, const float *sa, int M, const quota_weights *W, f16 *y,
+           int ldy, const f16 *res, int ldr, int32_t *acc, hipStream_t st)
 {
+    constexpr int BM = 32 * TM, BN = 128 * TN;
     int G = (W->K + QUOTA_GROUP_W - 1) / QUOTA_GROUP_W;
     int tiles_m = (M + BM - 1) / BM, tiles_n = (W->N + BN - 1) / BN;
-    size_t smem = sizeof(GemmSmem<BM, BN>);
-    auto kern = w4a4_gemm_kernel<BM, BN, ACC_OUT>;
-    static bool attr_set = false;      // once per tile shape; not a stream operation
-    if (smem > 48 * 1024 && !attr_set) {
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)smem) != hipSuccess)
-            return QUOTA_ERR_HIP;
-        attr_set = true;
-    }
     const double Md = M, Nd = W->N, Kd = W->K;
-    ProfScope prof(BM == 128 && BN == 128 ? QUOTA_K_GEMM_128X128
-                   : (BM == 64 && BN == 64 ? QUOTA_K_GEMM_64X64 : QUOTA_K_GEMM_OTHER),
-                   2.0 * Md * Nd * Kd,
+    ProfScope prof(kernel_id, 2.0 * Md * Nd * Kd,
                    Nd * Kd / 2 + 2.0 * Nd * G + Md * Kd / 2 + 4 * Md + 2.0 * Md * Nd * (res ? 2 : 1), st);
-    kern<<<dim3(tiles_m * tiles_n), dim3(256), smem, st>>>(
-        qa, sa, M, W->K, G, (const uint4 *)W->packed, (const f16 *)W->scales, W->N, y, ldy, res,
-        ldr, acc, tiles_m, tiles_n);
+    w4a4_gemm_kernel<TM, TN, DEPTH, ACC_OUT><<<dim3(tiles_m * tiles_n), dim3(256), 0, st>>>(
+        qa, sa, M, W->K, G, (const uint4 *)W->packed, (const f16 *)W->scales, W->N, y, ldy, res, ldr,
+        acc, tiles_m, tiles_n, (y && ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0) ? 1 : 0);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
 }
@@ -225,9 +286,13 @@ extern "C" int quota_w4a4_gemm(const uint8_t *qa, const float *sa, int M, const 
     hipStream_t st = (hipStream_t)stream;
     f16 *y = (f16 *)y_f16;
     const f16 *res = (const f16 *)residual_opt;
-    if (acc_i32_opt) return launch<64, 64, true>(qa, sa, M, W, y, ldy, res, ldr, acc_i32_opt, st);
-    long tiles_big = (long)((M + 127) / 128) * ((W->N + 127) / 128);
-    if (tiles_big >= 256)
-        return launch<128, 128, false>(qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
-    return launch<64, 64, false>(qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    if (acc_i32_opt)
+        return launch<2, 1, 2, true>(QUOTA_K_GEMM_OTHER, qa, sa, M, W, y, ldy, res, ldr, acc_i32_opt, st);
+    // wide tiles when they still give every CU work, narrow ones otherwise
+    const long mt64 = (M + 63) / 64, nt256 = (W->N + 255) / 256, nt128 = (W->N + 127) / 128;
+    if (mt64 * nt256 >= 192)
+        return launch<2, 2, 3, false>(QUOTA_K_GEMM_64X256, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    if (mt64 * nt128 >= 192)
+        return launch<2, 1, 3, false>(QUOTA_K_GEMM_64X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    return launch<1, 1, 3, false>(QUOTA_K_GEMM_OTHER, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
 }
