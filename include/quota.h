@@ -201,7 +201,7 @@ void quota_score_params_default(quota_score_params *p);
  * and rescales to [0,1] (0.5 for a flat metric); then
  * score = ((w_m*g_mag + w_c*g_inter) + w_s*g_intra) + w_r*g_res in fp32.
  * normed_opt receives the normalised metrics [4][B][Nv] (mag, inter, intra,
- * res).  Requires 0 <= pct_lo <= pct_hi <= 100, Nv <= 4096. */
+ * res).  Requires 0 <= pct_lo <= pct_hi <= 100, Nv <= 3072. */
 int quota_score_tokens(const float *sumsq, const float *ressq,
                        const float *cm_inter, const float *cm_intra, int B,
                        int Nv, const quota_score_params *p, float *score,
@@ -221,7 +221,7 @@ int quota_score_tokens_from_hidden(const void *v_f16, int B, int Nv, int d,
  * ties broken towards the lower index, emitted in ascending index order.
  * score fp32 [B][Nv]; keep_idx int32 [B][min(K,Nv)].  K is the integer budget
  * K_l = ceil(r_l * V0) (Eq. 5) -- the rounding is the recipe's job.  NaN
- * scores rank lowest.  Requires Nv <= 4096, K >= 0. */
+ * scores rank lowest.  Requires Nv <= 3072, K >= 0. */
 int quota_topk_prune(const float *score, int B, int Nv, int K,
                      int32_t *keep_idx, void *stream);
 
@@ -293,7 +293,7 @@ int quota_prefill_layer(const quota_layer *L, quota_state *st, int K_l,
  * because each shape is a separate kernel (and a separate profiler row). */
 enum {
     QUOTA_K_QUANTIZE_ACT = 0, QUOTA_K_RMSNORM_QUANTIZE_ACT, QUOTA_K_SILU_MUL_QUANTIZE_ACT,
-    QUOTA_K_GEMM_64X256, QUOTA_K_GEMM_64X128, QUOTA_K_GEMM_OTHER, QUOTA_K_ROPE_KV_QUANT,
+    QUOTA_K_GEMM_64X256, QUOTA_K_GEMM_64X128, QUOTA_K_GEMM_32X128, QUOTA_K_GEMM_OTHER, QUOTA_K_ROPE_KV_QUANT,
     QUOTA_K_KV_QUANT_APPEND, QUOTA_K_ATTENTION_FWD, QUOTA_K_ATTENTION_COLMASS,
     QUOTA_K_SCORE_TOKENS, QUOTA_K_TOPK_PRUNE, QUOTA_K_COMPACT_ROWS, QUOTA_K_QUANTIZE_WEIGHTS,
     QUOTA_K_PACK_WEIGHTS, QUOTA_KERNEL_COUNT

@@ -54,29 +54,40 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
     float m_run = -INFINITY, l_run = 0.0f;
 
     const int q_last_wg = min(q0 + 127, N - 1);
+    // Each thread stages 4 + 4 sixteen-byte pieces of a 64-key tile.  The pieces of the
+    // NEXT tile are fetched into registers before the current tile is consumed, so the
+    // global-memory latency overlaps the MFMAs instead of preceding them.
+    constexpr int PER = KT * CPR / 256;
+    Pack16 rk[PER], rv[PER];
+    auto fetch = [&](int kt0) {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int i = tid + 256 * j;
+            const int keyk = i / CPR, ck = i % CPR, keyv = i % KT, cv = i / KT;
+            rk[j].u = make_uint4(0, 0, 0, 0);
+            rv[j].u = make_uint4(0, 0, 0, 0);
+            if (kt0 + keyk < N)
+                rk[j].u = *reinterpret_cast<const uint4 *>(khat + base + (size_t)(kt0 + keyk) * d + 8 * ck);
+            if (kt0 + keyv < N)
+                rv[j].u = *reinterpret_cast<const uint4 *>(vhat + base + (size_t)(kt0 + keyv) * d + 8 * cv);
+        }
+    };
+    fetch(0);
     for (int kt0 = 0; kt0 <= q_last_wg; kt0 += KT) {
         __syncthreads();
-        // stage K rows (8-byte stores) and V transposed (2-byte stores, lane = key)
-        for (int i = tid; i < KT * CPR; i += 256) {
-            int key = i / CPR, c = i % CPR;
-            Pack16 kk;
-            kk.u = make_uint4(0, 0, 0, 0);
-            if (kt0 + key < N)
-                kk.u = *reinterpret_cast<const uint4 *>(khat + base + (size_t)(kt0 + key) * d + 8 * c);
-            uint2 *dst = reinterpret_cast<uint2 *>(&sm.k[key][8 * c]);
-            dst[0] = make_uint2(kk.w[0], kk.w[1]);
-            dst[1] = make_uint2(kk.w[2], kk.w[3]);
-        }
-        for (int i = tid; i < KT * CPR; i += 256) {
-            int key = i % KT, c = i / KT;
-            Pack16 vv;
-            vv.u = make_uint4(0, 0, 0, 0);
-            if (kt0 + key < N)
-                vv.u = *reinterpret_cast<const uint4 *>(vhat + base + (size_t)(kt0 + key) * d + 8 * c);
+        // K rows (8-byte stores) and V transposed (2-byte stores, lane = key)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sm.vt[8 * c + e][key] = vv.h[e];
+        for (int j = 0; j < PER; ++j) {
+            const int i = tid + 256 * j;
+            const int keyk = i / CPR, ck = i % CPR, keyv = i % KT, cv = i / KT;
+            uint2 *dst = reinterpret_cast<uint2 *>(&sm.k[keyk][8 * ck]);
+            dst[0] = make_uint2(rk[j].w[0], rk[j].w[1]);
+            dst[1] = make_uint2(rk[j].w[2], rk[j].w[3]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sm.vt[8 * cv + e][keyv] = rv[j].h[e];
         }
         __syncthreads();
+        if (kt0 + KT <= q_last_wg) fetch(kt0 + KT);
         if (kt0 > qw0 + 31) continue;        // tile entirely above this wave's diagonal
 
         f32x16 s[2];
@@ -177,20 +188,33 @@ __global__ __launch_bounds__(256) void colmass_kernel(
             kf[t] = f16x4{0, 0, 0, 0};
     }
     float acc_txt = 0.0f, acc_vis = 0.0f;
-    for (int qt0 = (kwg / KT) * KT; qt0 < N; qt0 += KT) {
-        __syncthreads();
-        for (int i = tid; i < KT * CPR; i += 256) {
-            int r = i / CPR, c = i % CPR;
-            Pack16 qq;
-            qq.u = make_uint4(0, 0, 0, 0);
+    constexpr int PER = KT * CPR / 256;
+    Pack16 rq[PER];
+    float rl = 0.0f;
+    auto fetch = [&](int qt0) {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int i = tid + 256 * j, r = i / CPR, c = i % CPR;
+            rq[j].u = make_uint4(0, 0, 0, 0);
             if (qt0 + r < N)
-                qq.u = *reinterpret_cast<const uint4 *>(q + base + (size_t)(qt0 + r) * d + 8 * c);
-            uint2 *dst = reinterpret_cast<uint2 *>(&sm.q[r][8 * c]);
-            dst[0] = make_uint2(qq.w[0], qq.w[1]);
-            dst[1] = make_uint2(qq.w[2], qq.w[3]);
+                rq[j].u = *reinterpret_cast<const uint4 *>(q + base + (size_t)(qt0 + r) * d + 8 * c);
         }
-        if (tid < KT) sm.lse[tid] = qt0 + tid < N ? lse2[((size_t)b * H + h) * N + qt0 + tid] : 0.0f;
+        if (tid < KT) rl = qt0 + tid < N ? lse2[((size_t)b * H + h) * N + qt0 + tid] : 0.0f;
+    };
+    const int qt_first = (kwg / KT) * KT;
+    fetch(qt_first);
+    for (int qt0 = qt_first; qt0 < N; qt0 += KT) {
         __syncthreads();
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int i = tid + 256 * j, r = i / CPR, c = i % CPR;
+            uint2 *dst = reinterpret_cast<uint2 *>(&sm.q[r][8 * c]);
+            dst[0] = make_uint2(rq[j].w[0], rq[j].w[1]);
+            dst[1] = make_uint2(rq[j].w[2], rq[j].w[3]);
+        }
+        if (tid < KT) sm.lse[tid] = rl;
+        __syncthreads();
+        if (qt0 + KT < N) fetch(qt0 + KT);
         if (qt0 + KT - 1 < kwg + wave * 32) continue;     // all queries before this wave's keys
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb) {
@@ -252,17 +276,16 @@ extern "C" size_t quota_attention_workspace_bytes(int B, int N, int H, int dh)
     return (size_t)B * H * N * sizeof(float) * 3;
 }
 
-extern "C" int quota_attention_prefill(const void *q_f16, const void *khat_f16,
-                                       const void *vhat_f16, int B, int N, int H, int dh,
-                                       int vis_begin, int Nv, void *o_f16, float *cm_inter,
-                                       float *cm_intra, void *ws, void *stream)
+int quota_internal_attention(const void *q_f16, const void *khat_f16, const void *vhat_f16, int B,
+                             int N, int H, int dh, int vis_begin, int Nv, void *o_f16,
+                             bool want_cues, void *ws, const float **partial_out, hipStream_t st)
 {
     if (!q_f16 || !khat_f16 || !vhat_f16 || !o_f16 || !ws) return QUOTA_ERR_NULL;
     if (B <= 0 || N < 0 || H <= 0 || vis_begin < 0 || Nv < 0 || vis_begin + Nv > N)
         return QUOTA_ERR_INVALID_ARG;
     if (dh != 64 && dh != 128) return QUOTA_ERR_SHAPE;
+    if (partial_out) *partial_out = nullptr;
     if (N == 0) return QUOTA_OK;
-    hipStream_t st = (hipStream_t)stream;
     float *lse2 = (float *)ws;
     float *partial = lse2 + (size_t)B * H * N;
     float scale_log2 = 1.4426950408889634f / sqrtf((float)dh);
@@ -277,7 +300,7 @@ extern "C" int quota_attention_prefill(const void *q_f16, const void *khat_f16,
             attn_fwd_kernel<64><<<g1, blk, 0, st>>>(q, k, v, N, H, (f16 *)o_f16, lse2, scale_log2);
     }
     QUOTA_RETURN_IF_LAUNCH_FAILED();
-    if (Nv > 0 && (cm_inter || cm_intra)) {
+    if (Nv > 0 && want_cues) {
         dim3 g2((Nv + 127) / 128, H, B);
         // (query, visual key) pairs under the causal mask
         const double pairs = (double)Nv * (N - vis_begin) - (double)Nv * (Nv - 1) / 2;
@@ -287,8 +310,24 @@ extern "C" int quota_attention_prefill(const void *q_f16, const void *khat_f16,
         else
             colmass_kernel<64><<<g2, blk, 0, st>>>(q, k, lse2, N, H, vis_begin, Nv, partial, scale_log2);
         QUOTA_RETURN_IF_LAUNCH_FAILED();
-        colmass_reduce_kernel<<<dim3((B * Nv + 255) / 256), blk, 0, st>>>(partial, B, H, Nv, cm_inter,
-                                                                          cm_intra);
+        if (partial_out) *partial_out = partial;
+    }
+    return QUOTA_OK;
+}
+
+extern "C" int quota_attention_prefill(const void *q_f16, const void *khat_f16,
+                                       const void *vhat_f16, int B, int N, int H, int dh,
+                                       int vis_begin, int Nv, void *o_f16, float *cm_inter,
+                                       float *cm_intra, void *ws, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const float *partial = nullptr;
+    int rc = quota_internal_attention(q_f16, khat_f16, vhat_f16, B, N, H, dh, vis_begin, Nv, o_f16,
+                                      cm_inter || cm_intra, ws, &partial, st);
+    if (rc != QUOTA_OK) return rc;
+    if (partial) {
+        colmass_reduce_kernel<<<dim3((B * Nv + 255) / 256), dim3(256), 0, st>>>(partial, B, H, Nv,
+                                                                                cm_inter, cm_intra);
         QUOTA_RETURN_IF_LAUNCH_FAILED();
     }
     return QUOTA_OK;

@@ -48,7 +48,9 @@ __device__ __forceinline__ int xcd_remap(int pid, int total)
 }
 
 // Workgroup tile (32*TM) x (128*TN); wave w owns columns [w*32*TN, (w+1)*32*TN).
-template <int TM, int TN, int DEPTH, bool ACC_OUT>
+// CH > 0: the LDS stage holds CH groups of activations, so the workgroup meets at a
+// barrier once per CH groups instead of once per group (DEPTH must be a multiple of CH).
+template <int TM, int TN, int DEPTH, int CH, bool PIPE, bool ACC_OUT>
 __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
     const uint8_t *__restrict__ qa, const float *__restrict__ sa, int M, int K, int G,
     const uint4 *__restrict__ wp, const f16 *__restrict__ sw, int N, f16 *__restrict__ y, int ldy,
@@ -58,9 +60,12 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
     constexpr int BM = 32 * TM, WN = 32 * TN, BN = 4 * WN;
     constexpr int LA = (BM * 4 + 255) / 256;         // 16-byte activation loads per thread per group
     constexpr int CROW = WN + 8;                     // halves per staged output row (16-byte pad)
-    constexpr int LDS_A = 2 * BM * AROW, LDS_C = 4 * 32 * CROW / 8;     // in uint4
+    constexpr int ASTAGE = BM * AROW + 2;            // uint4 per group of activations in LDS (+ spare slot)
+    constexpr bool CHUNK = CH > 0;
+    constexpr int CHN = CHUNK ? CH : 1;
+    static_assert(DEPTH % CHN == 0, "DEPTH must be a multiple of CH");
+    constexpr int LDS_A = 2 * CHN * ASTAGE, LDS_C = 4 * 32 * CROW / 8;     // in uint4
     __shared__ uint4 lds_raw[LDS_A > LDS_C ? LDS_A : LDS_C];
-    uint4 (*lds_a)[BM * AROW] = reinterpret_cast<uint4 (*)[BM * AROW]>(lds_raw);
 
     const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
     const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;
@@ -82,7 +87,7 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
         row = min(row, BM - 1);
         ca[j] = c * 16;
         oa[j] = (unsigned)(min(m0 + row, M - 1) - m0) * (unsigned)Kb;
-        la[j] = row * AROW + 2 * c;
+        la[j] = a_on[j] ? row * AROW + 2 * c : BM * AROW;   // spare slot after the tile
     }
     const uint8_t *abase = qa + (size_t)m0 * Kb;
     unsigned ow[TN], os[TN];        // uint4 / f16 index of this lane's weight chunk / scale in group 0
@@ -95,9 +100,9 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
         os[j] = (unsigned)n;
     }
 
-    uint4 ra[DEPTH][LA], rw[DEPTH][TN][2];
+    uint4 ra[CHUNK ? CHN : DEPTH][LA], rw[DEPTH][TN][2];
     f16 rs[DEPTH][TN];
-    auto load_group = [&](int stage, int g) {
+    auto load_w = [&](int stage, int g) {
         g = min(g, G - 1);
         const uint4 *wg = wp + (size_t)g * N * 4;        // uniform
         const f16 *sg = sw + (size_t)g * N;              // uniform
@@ -107,21 +112,22 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
             rw[stage][j][1] = wg[ow[j] + 1];
             rs[stage][j] = sg[os[j]];
         }
+    };
+    auto load_a = [&](int stage, int g) {
+        g = min(g, G - 1);
 #pragma unroll
         for (int j = 0; j < LA; ++j) {
             int kb = min(g * 64 + ca[j], Kb - 16);
             ra[stage][j] = *reinterpret_cast<const uint4 *>(abase + oa[j] + (unsigned)kb);
         }
     };
-    auto store_a = [&](int stage, int st) {
+    auto store_a = [&](int stage, uint4 *dst) {
 #pragma unroll
         for (int j = 0; j < LA; ++j) {
             uint4 lo, hi;
             unpack16(ra[stage][j], lo, hi);
-            if (LA * 256 == BM * 4 || a_on[j]) {
-                lds_a[st][la[j]] = lo;
-                lds_a[st][la[j] + 1] = hi;
-            }
+            dst[la[j]] = lo;            // threads without a row write the spare slot
+            dst[la[j] + 1] = hi;
         }
     };
 
@@ -140,9 +146,19 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
     const int fra = l32 * AROW + 4 * hl;       // this lane's A fragment (row l32 of a 32-row block)
 
 #pragma unroll
-    for (int s = 0; s < DEPTH; ++s) load_group(s, s);
-    store_a(0, 0);
+    for (int s = 0; s < DEPTH; ++s) load_w(s, s);
+    if (CHUNK) {
+#pragma unroll
+        for (int s = 0; s < CHN; ++s) load_a(s, s);
+#pragma unroll
+        for (int s = 0; s < CHN; ++s) store_a(s, lds_raw + s * ASTAGE);
+    } else {
+#pragma unroll
+        for (int s = 0; s < DEPTH; ++s) load_a(s, s);
+        store_a(0, lds_raw);
+    }
     __syncthreads();
+    int cb = 0;                     // CHUNK: which half of the LDS buffer holds the current groups
 
     // Software pipeline over the 32x32 sub-tiles, carried across groups: while the
     // matrix core runs the 4 MFMAs of a sub-tile, the vector ALU applies the group
@@ -160,58 +176,123 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
         }
     };
 
+    auto unpack_w = [&](int stage, int g, i32x4 (&fb)[TN][4], float (&swn)[TN]) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            swn[j] = (g < G && ncol[j] < N) ? (float)rs[stage][j] : 0.0f;
+            uint4 lo, hi;
+            unpack16(rw[stage][j][0], lo, hi);
+            fb[j][0] = as_i32x4(lo);
+            fb[j][1] = as_i32x4(hi);
+            unpack16(rw[stage][j][1], lo, hi);
+            fb[j][2] = as_i32x4(lo);
+            fb[j][3] = as_i32x4(hi);
+        }
+    };
+    auto read_a = [&](const uint4 *abuf, i32x4 (&fa)[TM][4]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) fa[i][ks] = as_i32x4(abuf[fra + 32 * i * AROW + ks]);
+    };
+    // MFMAs of group g with the scale of the previous sub-tile interleaved
+    auto mfma_group = [&](const i32x4 (&fa)[TM][4], const i32x4 (&fb)[TN][4], const float (&swn)[TN], int g) {
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int i = t / TN, j = t % TN;
+            i32x16 a = i32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                a = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i][ks], fb[j][ks], a, 0, 0, 0);
+            if (t == 0) scale_in(T - 1, pend, sw_prev, live_prev);
+            else scale_in(t - 1, pend, swn[(t - 1) % TN], g < G);
+            pend = a;
+        }
+        sw_prev = swn[(T - 1) % TN];
+        live_prev = g < G;
+    };
+
     const int Gpad = (G + DEPTH - 1) / DEPTH * DEPTH;
+    if constexpr (PIPE) {
+        // Group-level software pipeline for the narrow tiles, where a SIMD holds a single
+        // wave and nothing else hides latency: while the MFMAs of group g run, the weights
+        // of group g+1 are unpacked and its activation fragments are already on their way
+        // from LDS.  Scheduling barriers pin the three phases of an iteration; without them
+        // the fragment reads sink next to their first use and every MFMA waits on LDS.
+        static_assert(CHUNK && DEPTH % 2 == 0, "PIPE needs chunked staging and an even DEPTH");
+        i32x4 fbp[2][TN][4], fap[2][TM][4];
+        float swp[2][TN];
+        unpack_w(0, 0, fbp[0], swp[0]);
+        read_a(lds_raw, fap[0]);
+#pragma unroll 1
+        for (int g0 = 0; g0 < Gpad; g0 += DEPTH) {
+#pragma unroll
+            for (int s = 0; s < DEPTH; ++s) {
+                const int g = g0 + s, cur = s & 1, nxt = cur ^ 1, s1 = (s + 1) % DEPTH;
+                const bool chunk_end = s % CHN == CHN - 1;
+                if (s % CHN == 0) {             // activations of the next CH groups -> registers
+#pragma unroll
+                    for (int c = 0; c < CHN; ++c) load_a(c, g + CHN + c);
+                }
+                load_w(s, g + DEPTH);           // stage s was unpacked during the previous group
+                if (!chunk_end) read_a(lds_raw + (cb * CHN + s % CHN + 1) * ASTAGE, fap[nxt]);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_group(fap[cur], fbp[cur], swp[cur], g);
+                unpack_w(s1, g + 1, fbp[nxt], swp[nxt]);
+#pragma unroll
+                for (int q = 0; q < 4 * T; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, (ACC_OUT ? 12 : 8) + 6 / TM, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (chunk_end) {                // next CH groups of activations -> the other half
+#pragma unroll
+                    for (int c = 0; c < CHN; ++c) store_a(c, lds_raw + ((cb ^ 1) * CHN + c) * ASTAGE);
+                    __syncthreads();
+                    cb ^= 1;
+                    read_a(lds_raw + cb * CHN * ASTAGE, fap[nxt]);
+                }
+            }
+        }
+    } else {
 #pragma unroll 1
     for (int g0 = 0; g0 < Gpad; g0 += DEPTH) {
 #pragma unroll
         for (int s = 0; s < DEPTH; ++s) {
-            const int g = g0 + s, st = g & 1;
-            // activation fragments of group g from LDS (latency hidden by the unpack below)
-            i32x4 fa[TM][4];
+            const int g = g0 + s;
+            if (CHUNK && s % CHN == 0) {        // activations of the next CH groups -> registers
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) fa[i][ks] = as_i32x4(lds_a[st][fra + 32 * i * AROW + ks]);
-            // weights of group g: registers -> int8 B fragments
-            float swn[TN];
-            i32x4 fb[TN][4];
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                swn[j] = (g < G && ncol[j] < N) ? (float)rs[s][j] : 0.0f;
-                uint4 lo, hi;
-                unpack16(rw[s][j][0], lo, hi);
-                fb[j][0] = as_i32x4(lo);
-                fb[j][1] = as_i32x4(hi);
-                unpack16(rw[s][j][1], lo, hi);
-                fb[j][2] = as_i32x4(lo);
-                fb[j][3] = as_i32x4(hi);
+                for (int c = 0; c < CHN; ++c) load_a(c, g + CHN + c);
             }
+            const uint4 *abuf = lds_raw + (CHUNK ? (cb * CHN + s % CHN) : (g & 1)) * ASTAGE;
+            // activation fragments of group g from LDS, weights of group g from registers
+            i32x4 fa[TM][4], fb[TN][4];
+            float swn[TN];
+            read_a(abuf, fa);
+            unpack_w(s, g, fb, swn);
             // the stage that held group g is free again: prefetch group g + DEPTH into it
             // (its activation registers were stored to LDS one iteration ago)
-            load_group(s, g + DEPTH);
-
-#pragma unroll
-            for (int t = 0; t < T; ++t) {
-                const int i = t / TN, j = t % TN;
-                i32x16 a = i32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    a = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i][ks], fb[j][ks], a, 0, 0, 0);
-                if (t == 0) scale_in(T - 1, pend, sw_prev, live_prev);
-                else scale_in(t - 1, pend, swn[(t - 1) % TN], g < G);
-                pend = a;
-            }
-            sw_prev = swn[(T - 1) % TN];
-            live_prev = g < G;
-            store_a((s + 1) % DEPTH, st ^ 1);   // activations of group g+1 -> the other LDS buffer
-            // issue order: fragment reads, weight unpack, prefetch, then 1 MFMA : 8 VALU
+            load_w(s, g + DEPTH);
+            if (!CHUNK) load_a(s, g + DEPTH);
+            mfma_group(fa, fb, swn, g);
+            // issue order hint: 1 MFMA : 8 VALU
 #pragma unroll
             for (int q = 0; q < 4 * T; ++q) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x002, ACC_OUT ? 12 : 8, 0);
             }
-            __syncthreads();
+            if (!CHUNK) {           // activations of group g+1 -> the other LDS buffer
+                store_a((s + 1) % DEPTH, lds_raw + ((g & 1) ^ 1) * ASTAGE);
+                __syncthreads();
+            }
+            if (CHUNK && s % CHN == CHN - 1) {  // activations of the next CH groups -> the other half
+#pragma unroll
+                for (int c = 0; c < CHN; ++c) store_a(c, lds_raw + ((cb ^ 1) * CHN + c) * ASTAGE);
+                __syncthreads();
+                cb ^= 1;
+            }
         }
+    }
     }
     scale_in(T - 1, pend, sw_prev, live_prev);
 
@@ -253,7 +334,7 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
     }
 }
 
-template <int TM, int TN, int DEPTH, bool ACC_OUT>
+template <int TM, int TN, int DEPTH, int CH, bool PIPE, bool ACC_OUT>
 int launch(int kernel_id, const uint8_t *qa, const float *sa, int M, const quota_weights *W, f16 *y,
            int ldy, const f16 *res, int ldr, int32_t *acc, hipStream_t st)
 {
@@ -263,7 +344,7 @@ int launch(int kernel_id, const uint8_t *qa, const float *sa, int M, const quota
     const double Md = M, Nd = W->N, Kd = W->K;
     ProfScope prof(kernel_id, 2.0 * Md * Nd * Kd,
                    Nd * Kd / 2 + 2.0 * Nd * G + Md * Kd / 2 + 4 * Md + 2.0 * Md * Nd * (res ? 2 : 1), st);
-    w4a4_gemm_kernel<TM, TN, DEPTH, ACC_OUT><<<dim3(tiles_m * tiles_n), dim3(256), 0, st>>>(
+    w4a4_gemm_kernel<TM, TN, DEPTH, CH, PIPE, ACC_OUT><<<dim3(tiles_m * tiles_n), dim3(256), 0, st>>>(
         qa, sa, M, W->K, G, (const uint4 *)W->packed, (const f16 *)W->scales, W->N, y, ldy, res, ldr,
         acc, tiles_m, tiles_n, (y && ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0) ? 1 : 0);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
@@ -287,12 +368,18 @@ extern "C" int quota_w4a4_gemm(const uint8_t *qa, const float *sa, int M, const 
     f16 *y = (f16 *)y_f16;
     const f16 *res = (const f16 *)residual_opt;
     if (acc_i32_opt)
-        return launch<2, 1, 2, true>(QUOTA_K_GEMM_OTHER, qa, sa, M, W, y, ldy, res, ldr, acc_i32_opt, st);
-    // wide tiles when they still give every CU work, narrow ones otherwise
-    const long mt64 = (M + 63) / 64, nt256 = (W->N + 255) / 256, nt128 = (W->N + 127) / 128;
-    if (mt64 * nt256 >= 192)
-        return launch<2, 2, 3, false>(QUOTA_K_GEMM_64X256, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
-    if (mt64 * nt128 >= 192)
-        return launch<2, 1, 3, false>(QUOTA_K_GEMM_64X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
-    return launch<1, 1, 3, false>(QUOTA_K_GEMM_OTHER, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+        return launch<2, 1, 2, 0, false, true>(QUOTA_K_GEMM_OTHER, qa, sa, M, W, y, ldy, res, ldr, acc_i32_opt, st);
+    // Tile choice by how many workgroups a shape yields (2 fit on a CU): the wide tiles
+    // reuse each unpacked weight for 64 rows but need ~2 workgroups per CU to hide their
+    // latencies; below that the 32-row tiles spread the same work over more waves.
+    const long mt64 = (M + 63) / 64, mt32 = (M + 31) / 32;
+    const long nt256 = (W->N + 255) / 256, nt128 = (W->N + 127) / 128;
+    if (mt64 * nt256 >= 448)
+        return launch<2, 2, 3, 0, false, false>(QUOTA_K_GEMM_64X256, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    if (mt64 * nt128 >= 448)
+        return launch<2, 1, 4, 2, true, false>(QUOTA_K_GEMM_64X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    if (mt32 * nt128 > 256)
+        return launch<1, 1, 4, 4, true, false>(QUOTA_K_GEMM_32X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    // at most one workgroup per CU: a deeper weight prefetch is all that hides HBM latency
+    return launch<1, 1, 8, 4, true, false>(QUOTA_K_GEMM_32X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
 }

@@ -10,6 +10,19 @@ int quota_internal_score(const float *sumsq, const float *ressq, long stride_sq,
                          const float *cm_inter, const float *cm_intra, int B, int Nv,
                          const quota_score_params *p, float *score, float *normed, hipStream_t st);
 
+// score + top-k of the min(K, Nv) best tokens in one launch; cues either head-averaged
+// (cm_inter / cm_intra) or per head (partial [B][H][Nv][2], head mean taken in the kernel)
+int quota_internal_score_topk(const float *sumsq, const float *ressq, long stride_sq,
+                              const float *cm_inter, const float *cm_intra, const float *partial,
+                              int H, float *cm_out_inter, float *cm_out_intra, int B, int Nv,
+                              const quota_score_params *p, float *score, int K, int32_t *keep_idx,
+                              hipStream_t st);
+
+// attention + per-head column masses; partial_out (optional) [B][H][Nv][2] in the workspace
+int quota_internal_attention(const void *q_f16, const void *khat_f16, const void *vhat_f16, int B,
+                             int N, int H, int dh, int vis_begin, int Nv, void *o_f16,
+                             bool want_cues, void *ws, const float **partial_out, hipStream_t st);
+
 struct quota_compact_args {
     int B, N, vis_begin, Nv, k_keep, n_keep, d;
     const int32_t *keep_idx;

@@ -130,18 +130,29 @@ extern "C" int quota_prefill_layer(const quota_layer *L, quota_state *s, int K_l
     TRY(quota_rope_kv_quant(w.qkv, M, H, dh, s->pos, L->cosT, L->sinT, L->n_pos, w.q_rot, w.khat,
                             w.vhat, w.skc, w.sks, w.svc, w.svs, st));
     TRY(dump(t->q_rot, w.q_rot, (size_t)M * d * 2, st));
-    TRY(quota_attention_prefill(w.q_rot, w.khat, w.vhat, B, N, H, dh, vb, Nv, w.o, w.cm_inter,
-                                w.cm_intra, w.attn_ws, st));
+    const float *partial = nullptr;     // per-head column masses; their head mean is taken by the score kernel
+    TRY(quota_internal_attention(w.q_rot, w.khat, w.vhat, B, N, H, dh, vb, Nv, w.o, true, w.attn_ws,
+                                 &partial, st));
     TRY(dump(t->o, w.o, (size_t)M * d * 2, st));
     const f16 *o_used = t->inject_o ? (const f16 *)t->inject_o : w.o;
-    const float *cmi = t->inject_cm_inter ? t->inject_cm_inter : w.cm_inter;
-    const float *cmv = t->inject_cm_intra ? t->inject_cm_intra : w.cm_intra;
+    const bool inject_cm = t->inject_cm_inter && t->inject_cm_intra;
 
     // Eq. 6-9: cues -> G -> fused score -> top-K_l over the visual tokens
     if (Nv > 0) {
-        TRY(quota_internal_score(w.sumsq + vb, w.ressq + vb, N, cmi, cmv, B, Nv, p, w.score, nullptr,
-                                 st));
-        if (k_keep > 0) TRY(quota_topk_prune(w.score, B, Nv, k_keep, w.keep_idx, st));
+        if (inject_cm) {
+            // the library's own cues are still produced for the dump taps
+            if (t->cm_inter || t->cm_intra) {
+                TRY(quota_internal_score_topk(w.sumsq + vb, w.ressq + vb, N, nullptr, nullptr, partial, H,
+                                              w.cm_inter, w.cm_intra, B, Nv, p, w.score, 0, w.keep_idx, st));
+            }
+            TRY(quota_internal_score_topk(w.sumsq + vb, w.ressq + vb, N, t->inject_cm_inter,
+                                          t->inject_cm_intra, nullptr, 0, nullptr, nullptr, B, Nv, p,
+                                          w.score, k_keep, w.keep_idx, st));
+        } else {
+            TRY(quota_internal_score_topk(w.sumsq + vb, w.ressq + vb, N, nullptr, nullptr, partial, H,
+                                          w.cm_inter, w.cm_intra, B, Nv, p, w.score, k_keep, w.keep_idx,
+                                          st));
+        }
         if (t->sumsq || t->ressq) {
             long n = (long)B * Nv;
             dim3 g((unsigned)((n + 255) / 256)), blk(256);

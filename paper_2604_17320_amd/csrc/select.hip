@@ -1,14 +1,16 @@
 // Token scoring (Eq. 6-8) and deterministic budgeted top-k (Eq. 9).
-// One 256-thread workgroup per sequence; the Nv <= 4096 values live in LDS and
-// order statistics / the top-k threshold come from an exact 4-pass, 8-bit
-// radix select on order-preserving uint32 keys (LDS integer histograms, so the
-// result does not depend on execution order).
+// One 256-thread workgroup per sequence.  Order statistics and the top-k
+// threshold come from an exact 4-pass, 8-bit radix select on order-preserving
+// uint32 keys, run by ONE WAVE with a private 256-bin LDS histogram (integer
+// atomics, so the result does not depend on execution order; no workgroup
+// barrier inside the select).  The four metrics are normalised in parallel,
+// one wave each; the top-k runs on wave 0.
 #include "common.h"
 #include "internal.h"
 
 namespace {
 
-constexpr int MAXV = 4096;
+constexpr int MAXV = 3072;
 
 // ascending uint32 order == ascending float order; -0 is folded onto +0
 __device__ __forceinline__ uint32_t float_key(float f)
@@ -23,46 +25,45 @@ __device__ __forceinline__ float key_float(uint32_t k)
     return __uint_as_float(u);
 }
 
-// Exact k-th smallest (0-based rank) of keys[0..n), whole block cooperates.
-// hist: 256 ints of LDS; bc: 2 ints of LDS.  All threads return the key.
-__device__ uint32_t radix_select(const uint32_t *keys, int n, int rank, int *hist, int *bc)
+// Exact k-th smallest (0-based rank) of the n keys key_at(i), computed by the
+// calling wave alone.  hist: 256 ints of LDS private to the wave.  All lanes
+// return the key.
+template <typename KeyAt>
+__device__ uint32_t wave_radix_select(KeyAt key_at, int n, int rank, volatile int *hist)
 {
+    const int lane = threadIdx.x & 63;
     uint32_t prefix = 0, mask = 0;
     int remaining = rank;
     for (int shift = 24; shift >= 0; shift -= 8) {
-        __syncthreads();
-        hist[threadIdx.x] = 0;
-        __syncthreads();
-        for (int i = threadIdx.x; i < n; i += 256) {
-            uint32_t k = keys[i];
-            if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 0xFF], 1);
-        }
-        __syncthreads();
-        if (threadIdx.x < 64) {          // wave 0 scans the 256 bins, 4 per lane
-            int l = threadIdx.x;
-            int c0 = hist[4 * l], c1 = hist[4 * l + 1], c2 = hist[4 * l + 2], c3 = hist[4 * l + 3];
-            int s = c0 + c1 + c2 + c3, incl = s;
 #pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                int t = __shfl_up(incl, off, 64);
-                if (l >= off) incl += t;
-            }
-            int excl = incl - s;
-            if (remaining >= excl && remaining < incl) {   // exactly one lane
-                int r = remaining - excl, digit = 4 * l;
-                if (r >= c0) { r -= c0; ++digit;
-                    if (r >= c1) { r -= c1; ++digit;
-                        if (r >= c2) { r -= c2; ++digit; } } }
-                bc[0] = digit;
-                bc[1] = r;
-            }
+        for (int b = 0; b < 4; ++b) hist[4 * lane + b] = 0;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        for (int i = lane; i < n; i += 64) {
+            uint32_t k = key_at(i);
+            if ((k & mask) == prefix) atomicAdd(const_cast<int *>(&hist[(k >> shift) & 0xFF]), 1);
         }
-        __syncthreads();
-        prefix |= (uint32_t)bc[0] << shift;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        int c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
+        int s = c0 + c1 + c2 + c3, incl = s;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            int t = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += t;
+        }
+        int excl = incl - s;
+        bool mine = remaining >= excl && remaining < incl;      // exactly one lane
+        int r = remaining - excl, digit = 4 * lane;
+        if (r >= c0) { r -= c0; ++digit;
+            if (r >= c1) { r -= c1; ++digit;
+                if (r >= c2) { r -= c2; ++digit; } } }
+        unsigned long long who = __ballot(mine);
+        int src = __ffsll((long long)who) - 1;
+        digit = __shfl(digit, src, 64);
+        remaining = __shfl(r, src, 64);
+        prefix |= (uint32_t)digit << shift;
         mask |= 0xFFu << shift;
-        remaining = bc[1];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     }
-    __syncthreads();
     return prefix;
 }
 
@@ -76,81 +77,170 @@ __device__ __forceinline__ float robust_unit(float m, float lo, float hi)
     return fminf(fmaxf(v, 0.0f), 1.0f);
 }
 
-__device__ __forceinline__ float metric_value(int k, size_t isq, size_t icm,
-                                              const float *__restrict__ sumsq,
-                                              const float *__restrict__ ressq,
-                                              const float *__restrict__ cm_inter,
-                                              const float *__restrict__ cm_intra)
-{
-    switch (k) {
-    case 0: return sqrtf(sumsq[isq]);          // m_mag
-    case 1: return cm_inter[icm];              // m_inter
-    case 2: return cm_intra[icm];              // m_intra
-    default: return sqrtf(ressq[isq]);         // m_res
-    }
-}
+struct MetricSrc {
+    const float *sumsq, *ressq, *cm_inter, *cm_intra;
+    const float *partial;   // optional per-head column masses [B][H][Nv][2] (text, visual)
+    int H;
+    float *cm_out_inter, *cm_out_intra;     // optional [B][Nv] outputs of the head means
+    size_t osq, ocm;        // offsets of this sequence in the sumsq/ressq and cm arrays
+};
 
-__global__ __launch_bounds__(256) void score_kernel(
-    const float *__restrict__ sumsq, const float *__restrict__ ressq, long stride_sq,
-    const float *__restrict__ cm_inter, const float *__restrict__ cm_intra, int B, int Nv,
-    quota_score_params p, float *__restrict__ score, float *__restrict__ normed)
+// Loads the four Eq. 6 metrics of sequence b into LDS as order-preserving keys
+// (all loads of a thread are independent, so one memory latency covers them),
+// then finds the percentile bounds (one wave per metric, keys in LDS), then
+// fuses the score of every token.  mk: 4*MAXV keys, hist: 4*256 ints, lohi: 8 floats.
+__device__ void score_phase(const MetricSrc &src, int B, int Nv, int b, const quota_score_params &p,
+                            float *__restrict__ score, float *__restrict__ normed, uint32_t *mk,
+                            int *hist, float *lohi)
 {
-    __shared__ uint32_t keys[MAXV];
-    __shared__ int hist[256];
-    __shared__ int bc[2];
-    const int b = blockIdx.x;
-    const int r_lo = (p.pct_lo * (Nv - 1) + 50) / 100, r_hi = (p.pct_hi * (Nv - 1) + 50) / 100;
-    float lo[4], hi[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        __syncthreads();
-        for (int i = threadIdx.x; i < Nv; i += 256)
-            keys[i] = float_key(metric_value(k, (size_t)b * stride_sq + i, (size_t)b * Nv + i, sumsq,
-                                             ressq, cm_inter, cm_intra));
-        lo[k] = key_float(radix_select(keys, Nv, r_lo, hist, bc));
-        hi[k] = key_float(radix_select(keys, Nv, r_hi, hist, bc));
-    }
+    const int wave = threadIdx.x >> 6;
     for (int i = threadIdx.x; i < Nv; i += 256) {
-        size_t isq = (size_t)b * stride_sq + i, icm = (size_t)b * Nv + i;
-        float g0 = robust_unit(metric_value(0, isq, icm, sumsq, ressq, cm_inter, cm_intra), lo[0], hi[0]);
-        float g1 = robust_unit(metric_value(1, isq, icm, sumsq, ressq, cm_inter, cm_intra), lo[1], hi[1]);
-        float g2 = robust_unit(metric_value(2, isq, icm, sumsq, ressq, cm_inter, cm_intra), lo[2], hi[2]);
-        float g3 = robust_unit(metric_value(3, isq, icm, sumsq, ressq, cm_inter, cm_intra), lo[3], hi[3]);
-        float a = p.w_m * g0;
-        float c = p.w_c * g1;
-        float s = p.w_s * g2;
-        float r = p.w_r * g3;
-        float acc = a + c;
-        acc = acc + s;
-        acc = acc + r;
-        score[icm] = acc;
-        if (normed) {
-            size_t plane = (size_t)B * Nv;
-            normed[0 * plane + icm] = g0;
-            normed[1 * plane + icm] = g1;
-            normed[2 * plane + icm] = g2;
-            normed[3 * plane + icm] = g3;
+        float m_inter, m_intra;
+        if (src.partial) {      // head mean in head order: (sum_h partial) * (1/H)
+            float st = 0.0f, sv = 0.0f;
+            const float2 *pp = reinterpret_cast<const float2 *>(src.partial) + (size_t)b * src.H * Nv + i;
+            for (int h0 = 0; h0 < src.H; h0 += 8) {        // 8 independent loads in flight, adds in head order
+                float2 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    v[u] = h0 + u < src.H ? pp[(size_t)(h0 + u) * Nv] : make_float2(0.0f, 0.0f);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (h0 + u < src.H) { st += v[u].x; sv += v[u].y; }
+            }
+            const float invH = 1.0f / (float)src.H;
+            m_inter = st * invH;
+            m_intra = sv * invH;
+            if (src.cm_out_inter) src.cm_out_inter[src.ocm + i] = m_inter;
+            if (src.cm_out_intra) src.cm_out_intra[src.ocm + i] = m_intra;
+        } else {
+            m_inter = src.cm_inter[src.ocm + i];
+            m_intra = src.cm_intra[src.ocm + i];
+        }
+        mk[0 * MAXV + i] = float_key(sqrtf(src.sumsq[src.osq + i]));    // m_mag
+        mk[1 * MAXV + i] = float_key(m_inter);
+        mk[2 * MAXV + i] = float_key(m_intra);
+        mk[3 * MAXV + i] = float_key(sqrtf(src.ressq[src.osq + i]));    // m_res
+    }
+    __syncthreads();
+    const int r_lo = (p.pct_lo * (Nv - 1) + 50) / 100, r_hi = (p.pct_hi * (Nv - 1) + 50) / 100;
+    {
+        const uint32_t *keys = mk + wave * MAXV;    // 4 waves <-> 4 metrics
+        auto key_at = [&](int i) { return keys[i]; };
+        uint32_t klo = wave_radix_select(key_at, Nv, r_lo, hist + 256 * wave);
+        uint32_t khi = wave_radix_select(key_at, Nv, r_hi, hist + 256 * wave);
+        if ((threadIdx.x & 63) == 0) { lohi[2 * wave] = key_float(klo); lohi[2 * wave + 1] = key_float(khi); }
+    }
+    __syncthreads();
+    float sc[MAXV / 256];
+#pragma unroll
+    for (int r = 0; r < MAXV / 256; ++r) {
+        const int i = threadIdx.x + 256 * r;
+        if (i < Nv) {
+            float g0 = robust_unit(key_float(mk[0 * MAXV + i]), lohi[0], lohi[1]);
+            float g1 = robust_unit(key_float(mk[1 * MAXV + i]), lohi[2], lohi[3]);
+            float g2 = robust_unit(key_float(mk[2 * MAXV + i]), lohi[4], lohi[5]);
+            float g3 = robust_unit(key_float(mk[3 * MAXV + i]), lohi[6], lohi[7]);
+            float a = p.w_m * g0;
+            float c = p.w_c * g1;
+            float s = p.w_s * g2;
+            float rr = p.w_r * g3;
+            float acc = a + c;
+            acc = acc + s;
+            acc = acc + rr;
+            size_t o = (size_t)b * Nv + i;
+            score[o] = acc;
+            sc[r] = acc;
+            if (normed) {
+                size_t plane = (size_t)B * Nv;
+                normed[0 * plane + o] = g0;
+                normed[1 * plane + o] = g1;
+                normed[2 * plane + o] = g2;
+                normed[3 * plane + o] = g3;
+            }
         }
     }
+    __syncthreads();            // every metric key has been read: slot 0 becomes the score keys
+#pragma unroll
+    for (int r = 0; r < MAXV / 256; ++r) {
+        const int i = threadIdx.x + 256 * r;
+        if (i < Nv) mk[i] = (sc[r] != sc[r]) ? 0u : float_key(sc[r]);
+    }
 }
 
-// block-wide exclusive scan of one int per thread (256 threads)
-__device__ __forceinline__ int block_excl_scan(int v, int *sm, int *total)
+__device__ __forceinline__ int wave_excl_scan(int v, int *total)
 {
-    int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
     int incl = v;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
         int t = __shfl_up(incl, off, 64);
         if (lane >= off) incl += t;
     }
+    *total = __shfl(incl, 63, 64);
+    return incl - v;
+}
+
+// Top-k of keys[0..Nv) (LDS) by the calling wave: K largest, ties to the lower
+// index, ascending output.  Requires 0 < K < Nv.
+__device__ void topk_phase(const uint32_t *keys, int Nv, int K, int32_t *__restrict__ out, int *hist)
+{
+    const int lane = threadIdx.x & 63;
+    auto key_at = [&](int i) { return keys[i]; };
+    // threshold = K-th largest = rank (Nv - K) in ascending order
+    const uint32_t thr = wave_radix_select(key_at, Nv, Nv - K, hist);
+    // each lane owns a contiguous index range so the scans follow index order
+    const int per = (Nv + 63) / 64;
+    const int i0 = min(lane * per, Nv), i1 = min(i0 + per, Nv);
+    int n_gt = 0, n_eq = 0;
+    for (int i = i0; i < i1; ++i) {
+        n_gt += keys[i] > thr;
+        n_eq += keys[i] == thr;
+    }
+    int tot_gt, tot_eq;
+    const int eq_before = wave_excl_scan(n_eq, &tot_eq);
+    wave_excl_scan(n_gt, &tot_gt);
+    const int need = K - tot_gt;                       // ties taken, lowest indices first
+    int n_sel = 0, e = eq_before;
+    for (int i = i0; i < i1; ++i) {
+        uint32_t k = keys[i];
+        n_sel += (k > thr) || (k == thr && e < need);
+        e += k == thr;
+    }
+    int tot_sel;
+    int pos = wave_excl_scan(n_sel, &tot_sel);
+    e = eq_before;
+    for (int i = i0; i < i1; ++i) {
+        uint32_t k = keys[i];
+        if ((k > thr) || (k == thr && e < need)) out[pos++] = i;
+        e += k == thr;
+    }
+}
+
+// K < 0: score only.  When K >= 0 the indices of the min(K, Nv) best tokens of
+// sequence b go to keep_idx[b][0..min(K,Nv)).
+__global__ __launch_bounds__(256) void score_topk_kernel(MetricSrc src, long stride_sq, int B, int Nv,
+                                                         quota_score_params p,
+                                                         float *__restrict__ score,
+                                                         float *__restrict__ normed, int K,
+                                                         int32_t *__restrict__ keep_idx)
+{
+    __shared__ uint32_t mk[4 * MAXV];
+    __shared__ int hist[4 * 256];
+    __shared__ float lohi[8];
+    const int b = blockIdx.x;
+    src.osq = (size_t)b * stride_sq;
+    src.ocm = (size_t)b * Nv;
+    score_phase(src, B, Nv, b, p, score, normed, mk, hist, lohi);
+    if (K < 0) return;
+    const int k = K < Nv ? K : Nv;
+    int32_t *out = keep_idx + (size_t)b * k;
+    if (k == Nv) {
+        for (int i = threadIdx.x; i < Nv; i += 256) out[i] = i;
+        return;
+    }
     __syncthreads();
-    if (lane == 63) sm[w] = incl;
-    __syncthreads();
-    int base = 0;
-    for (int i = 0; i < w; ++i) base += sm[i];
-    *total = sm[0] + sm[1] + sm[2] + sm[3];
-    return base + incl - v;
+    if (threadIdx.x < 64 && k > 0) topk_phase(mk, Nv, k, out, hist);
 }
 
 __global__ __launch_bounds__(256) void topk_kernel(const float *__restrict__ score, int Nv, int K,
@@ -158,8 +248,6 @@ __global__ __launch_bounds__(256) void topk_kernel(const float *__restrict__ sco
 {
     __shared__ uint32_t keys[MAXV];
     __shared__ int hist[256];
-    __shared__ int bc[2];
-    __shared__ int sc[4];
     const int b = blockIdx.x;
     int32_t *out = keep_idx + (size_t)b * K;
     if (K >= Nv) {          // host passes K <= Nv; K == Nv keeps every token
@@ -170,34 +258,18 @@ __global__ __launch_bounds__(256) void topk_kernel(const float *__restrict__ sco
         float f = score[(size_t)b * Nv + i];
         keys[i] = (f != f) ? 0u : float_key(f);       // NaN ranks lowest
     }
-    // threshold = K-th largest = rank (Nv - K) in ascending order
-    const uint32_t thr = radix_select(keys, Nv, Nv - K, hist, bc);
-    // each thread owns a contiguous index range so scans follow index order
-    const int per = (Nv + 255) / 256;
-    const int i0 = threadIdx.x * per, i1 = min(i0 + per, Nv);
-    int n_gt = 0, n_eq = 0;
-    for (int i = i0; i < i1; ++i) {
-        n_gt += keys[i] > thr;
-        n_eq += keys[i] == thr;
-    }
-    int tot_gt, tot_eq;
-    int eq_before = block_excl_scan(n_eq, sc, &tot_eq);
-    block_excl_scan(n_gt, sc, &tot_gt);
-    const int need = K - tot_gt;                       // ties taken, lowest indices first
-    int n_sel = 0, e = eq_before;
-    for (int i = i0; i < i1; ++i) {
-        uint32_t k = keys[i];
-        n_sel += (k > thr) || (k == thr && e < need);
-        e += k == thr;
-    }
-    int tot_sel;
-    int pos = block_excl_scan(n_sel, sc, &tot_sel);
-    e = eq_before;
-    for (int i = i0; i < i1; ++i) {
-        uint32_t k = keys[i];
-        if ((k > thr) || (k == thr && e < need)) out[pos++] = i;
-        e += k == thr;
-    }
+    __syncthreads();
+    if (threadIdx.x < 64) topk_phase(keys, Nv, K, out, hist);
+}
+
+int check_score_args(const float *sumsq, const float *ressq, const float *cm_inter,
+                     const float *cm_intra, int B, int Nv, const quota_score_params *p, float *score)
+{
+    if (!sumsq || !ressq || !cm_inter || !cm_intra || !p || !score) return QUOTA_ERR_NULL;
+    if (B <= 0 || Nv < 0 || p->pct_lo < 0 || p->pct_hi > 100 || p->pct_lo > p->pct_hi)
+        return QUOTA_ERR_INVALID_ARG;
+    if (Nv > MAXV) return QUOTA_ERR_SHAPE;
+    return QUOTA_OK;
 }
 
 }  // namespace
@@ -206,14 +278,39 @@ int quota_internal_score(const float *sumsq, const float *ressq, long stride_sq,
                          const float *cm_inter, const float *cm_intra, int B, int Nv,
                          const quota_score_params *p, float *score, float *normed, hipStream_t st)
 {
-    if (!sumsq || !ressq || !cm_inter || !cm_intra || !p || !score) return QUOTA_ERR_NULL;
-    if (B <= 0 || Nv < 0 || p->pct_lo < 0 || p->pct_hi > 100 || p->pct_lo > p->pct_hi)
+    int rc = check_score_args(sumsq, ressq, cm_inter, cm_intra, B, Nv, p, score);
+    if (rc != QUOTA_OK) return rc;
+    if (Nv == 0) return QUOTA_OK;
+    ProfScope prof(QUOTA_K_SCORE_TOKENS, 0, 20.0 * B * Nv, st);
+    MetricSrc src{sumsq, ressq, cm_inter, cm_intra, nullptr, 0, nullptr, nullptr, 0, 0};
+    score_topk_kernel<<<dim3(B), dim3(256), 0, st>>>(src, stride_sq, B, Nv, *p, score, normed, -1,
+                                                     nullptr);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    return QUOTA_OK;
+}
+
+// score + top-k in one launch (the layer's path).  The attention cues come either as
+// head-averaged arrays (cm_inter / cm_intra) or, when `partial` is given, as the
+// per-head column masses [B][H][Nv][2] whose head mean is taken here; cm_out_* (optional)
+// then receive the head means.
+int quota_internal_score_topk(const float *sumsq, const float *ressq, long stride_sq,
+                              const float *cm_inter, const float *cm_intra, const float *partial,
+                              int H, float *cm_out_inter, float *cm_out_intra, int B, int Nv,
+                              const quota_score_params *p, float *score, int K, int32_t *keep_idx,
+                              hipStream_t st)
+{
+    if (!sumsq || !ressq || !p || !score || !keep_idx) return QUOTA_ERR_NULL;
+    if (!partial && (!cm_inter || !cm_intra)) return QUOTA_ERR_NULL;
+    if (B <= 0 || Nv < 0 || K < 0 || (partial && H <= 0) || p->pct_lo < 0 || p->pct_hi > 100 ||
+        p->pct_lo > p->pct_hi)
         return QUOTA_ERR_INVALID_ARG;
     if (Nv > MAXV) return QUOTA_ERR_SHAPE;
     if (Nv == 0) return QUOTA_OK;
-    ProfScope prof(QUOTA_K_SCORE_TOKENS, 0, 20.0 * B * Nv, st);
-    score_kernel<<<dim3(B), dim3(256), 0, st>>>(sumsq, ressq, stride_sq, cm_inter, cm_intra, B, Nv,
-                                                *p, score, normed);
+    ProfScope prof(QUOTA_K_SCORE_TOKENS, 0,
+                   (partial ? 8.0 * H + 8 : 20.0) * B * Nv + 4.0 * B * (K < Nv ? K : Nv), st);
+    MetricSrc src{sumsq, ressq, cm_inter, cm_intra, partial, H, cm_out_inter, cm_out_intra, 0, 0};
+    score_topk_kernel<<<dim3(B), dim3(256), 0, st>>>(src, stride_sq, B, Nv, *p, score, nullptr, K,
+                                                     keep_idx);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
 }

@@ -291,7 +291,7 @@ def _metrics(B, Nv, seed):
             r.uniform(0, 0.2, (B, Nv)).astype(np.float32), r.uniform(0, 3, (B, Nv)).astype(np.float32))
 
 
-@pytest.mark.parametrize("B,Nv", [(1, 64), (3, 576), (2, 2880), (1, 1), (1, 4096), (2, 7)])
+@pytest.mark.parametrize("B,Nv", [(1, 64), (3, 576), (2, 2880), (1, 1), (1, 3072), (2, 7)])
 def test_score_tokens_bit_exact(qb, B, Nv):
     ss, rs, ci, cv = _metrics(B, Nv, 61)
     if Nv > 4:
@@ -324,7 +324,7 @@ def test_score_tokens_from_hidden(qb):
     assert np.array_equal(host(sc), sc_ref)
 
 
-@pytest.mark.parametrize("B,Nv", [(1, 64), (3, 576), (2, 2880), (1, 4096), (2, 5)])
+@pytest.mark.parametrize("B,Nv", [(1, 64), (3, 576), (2, 2880), (1, 3072), (2, 5)])
 def test_topk_prune_bit_exact(qb, B, Nv):
     r = wl.rng(71, "topk", B, Nv)
     sc = (np.round(r.uniform(0, 1, (B, Nv)) * 50) / 50).astype(np.float32)     # plenty of ties
