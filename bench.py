@@ -46,6 +46,20 @@ def build_stack(shape, seed, budgets, keep_plain_layers=()):
     return stack, (cos, sin)
 
 
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed counter profile (two rocprofv3 --pmc
+    passes, FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_c3_stack.txt")
+    try:
+        with open(path) as f:
+            rec = json.load(f)["kernels"].get(kernel)
+    except (OSError, ValueError, KeyError):
+        return None
+    return rec and dict(bytes_per_launch=rec["fetch_bytes"] + rec["write_bytes"], fetch_bytes=rec["fetch_bytes"],
+                        write_bytes=rec["write_bytes"], algorithmic_bytes=rec.get("algorithmic_bytes"),
+                        source="profiles/hbm_traffic_c3_stack.txt")
+
+
 def cpu_baseline(shape, stack, budgets, rope, sample_layers, seed):
     """The oracle, as it stands, on a bounded sample: a few layers of the stack, each fed a
     synthetic hidden state with the row count that layer sees in the real run."""
@@ -93,6 +107,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--profile-steps", type=int, default=3)
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one plain elementwise copy of this many MiB (read + write), untimed: "
+                         "the known-size kernel that HBM traffic counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on ONE GPU (no sharding, no collectives); --gpus N>1 is not "
@@ -115,6 +132,13 @@ def main():
 
     def step():
         return stack.run(x0, pos0)
+
+    if args.calibration_copy_mib:
+        src = torch.ones(args.calibration_copy_mib << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(max(args.warmup, 1)):
         step()
@@ -151,33 +175,42 @@ def main():
     torch.cuda.synchronize()
     eager_ms = (time.perf_counter() - t0) * 1e3 / max(1, args.steps // 5)
 
-    # per-kernel HIP-event timing over full eager steps
+    # per-kernel HIP-event timing over full eager steps.  An event pair around a launch also
+    # reads the fixed cost of the pair itself (a few us); that cost is measured here with
+    # empty kernels and taken off every launch, so the figures are the kernels' own run
+    # times, as a kernel trace reports them.
+    bracket_ms, empty_kernel_ms = qb.quota_profile_bracket_ms(64)
     kernels_per_step = 20 * shape.layers
     qb.quota_profile_begin(kernels_per_step * args.profile_steps + 16)
     for _ in range(args.profile_steps):
         step()
     stats = qb.quota_profile_collect()
+    for s in stats.values():
+        s["raw_ms"] = s["total_ms"]
+        s["total_ms"] = max(s["total_ms"] - bracket_ms * s["launches"], 1e-9)
     kern = {}
     for name, s in stats.items():
         us = s["total_ms"] * 1e3 / s["launches"]
         kern[name] = dict(launches_per_step=s["launches"] // args.profile_steps, avg_us=round(us, 2),
+                          avg_us_with_bracket=round(s["raw_ms"] * 1e3 / s["launches"], 2),
                           step_ms=round(s["total_ms"] / args.profile_steps, 4),
                           GBps=round(s["bytes"] / (s["total_ms"] * 1e-3) / 1e9, 1) if s["total_ms"] else None,
                           TOPs=round(s["ops"] / (s["total_ms"] * 1e-3) / 1e12, 1) if s["ops"] else None)
     dom = max(stats, key=lambda k: stats[k]["total_ms"])
     ds = stats[dom]
+    per_launch = dict(avg_launch_us=round(ds["total_ms"] * 1e3 / ds["launches"], 2),
+                      avg_launch_us_with_bracket=round(ds["raw_ms"] * 1e3 / ds["launches"], 2),
+                      event_bracket_us=round(bracket_ms * 1e3, 2), empty_kernel_us=round(empty_kernel_ms * 1e3, 2),
+                      launches_per_step=ds["launches"] // args.profile_steps)
+    traffic = measured_traffic(dom)
     if ds["ops"] and dom.startswith("w4a4_gemm"):
         achieved = ds["ops"] / (ds["total_ms"] * 1e-3) / 1e12
         roofline = dict(kernel=dom, bound="mfma", achieved=round(achieved, 1), peak=PEAK_INT8_TOPS,
-                        unit="TOP/s", frac=round(achieved / PEAK_INT8_TOPS, 4), traffic=None,
-                        avg_launch_us=round(ds["total_ms"] * 1e3 / ds["launches"], 2),
-                        launches_per_step=ds["launches"] // args.profile_steps)
+                        unit="TOP/s", frac=round(achieved / PEAK_INT8_TOPS, 4), traffic=traffic, **per_launch)
     else:
         achieved = ds["bytes"] / (ds["total_ms"] * 1e-3) / 1e9
         roofline = dict(kernel=dom, bound="hbm", achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=round(achieved / PEAK_HBM_GBS, 4), traffic=None,
-                        avg_launch_us=round(ds["total_ms"] * 1e3 / ds["launches"], 2),
-                        launches_per_step=ds["launches"] // args.profile_steps)
+                        frac=round(achieved / PEAK_HBM_GBS, 4), traffic=traffic, **per_launch)
     gemm_ops = sum(s["ops"] for n, s in stats.items() if n.startswith("w4a4_gemm"))
     gemm_ms = sum(s["total_ms"] for n, s in stats.items() if n.startswith("w4a4_gemm"))
 

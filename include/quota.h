@@ -293,7 +293,8 @@ int quota_prefill_layer(const quota_layer *L, quota_state *st, int K_l,
  * because each shape is a separate kernel (and a separate profiler row). */
 enum {
     QUOTA_K_QUANTIZE_ACT = 0, QUOTA_K_RMSNORM_QUANTIZE_ACT, QUOTA_K_SILU_MUL_QUANTIZE_ACT,
-    QUOTA_K_GEMM_64X256, QUOTA_K_GEMM_64X128, QUOTA_K_GEMM_32X128, QUOTA_K_GEMM_OTHER, QUOTA_K_ROPE_KV_QUANT,
+    QUOTA_K_GEMM_64X256, QUOTA_K_GEMM_64X128, QUOTA_K_GEMM_32X128, QUOTA_K_GEMM_32X128_DEEP,
+    QUOTA_K_GEMM_OTHER, QUOTA_K_ROPE_KV_QUANT,
     QUOTA_K_KV_QUANT_APPEND, QUOTA_K_ATTENTION_FWD, QUOTA_K_ATTENTION_COLMASS,
     QUOTA_K_SCORE_TOKENS, QUOTA_K_TOPK_PRUNE, QUOTA_K_COMPACT_ROWS, QUOTA_K_QUANTIZE_WEIGHTS,
     QUOTA_K_PACK_WEIGHTS, QUOTA_KERNEL_COUNT
@@ -321,6 +322,15 @@ int quota_profile_begin(int max_launches);
 /* Stops recording, waits for the recorded events, fills
  * stats[QUOTA_KERNEL_COUNT] (host) and frees the events. */
 int quota_profile_collect(quota_kernel_stat *stats);
+
+/* The fixed cost of an event pair itself.  On `stream`, brackets one empty
+ * kernel, then two, between a pair of HIP events, `reps` (1..1024) times each,
+ * and takes medians t1 and t2.  t2 - t1 is what one more empty kernel adds
+ * (*empty_kernel_ms, optional); t1 - (t2 - t1) is what the bracket costs with
+ * no kernel in it (*bracket_ms) -- the part of quota_profile_collect's
+ * total_ms, per launch, that is not the kernel's.  Both are host pointers.
+ * Allocates events: benchmark use only. */
+int quota_profile_bracket_ms(int reps, void *stream, float *bracket_ms, float *empty_kernel_ms);
 
 #ifdef __cplusplus
 }

@@ -62,7 +62,7 @@ class KernelStat(C.Structure):
     _fields_ = [("launches", C.c_long), ("total_ms", C.c_double), ("ops", C.c_double), ("bytes", C.c_double)]
 
 
-KERNEL_COUNT = 16
+KERNEL_COUNT = 17
 
 _lib = None
 
@@ -219,6 +219,14 @@ def quota_profile_begin(max_launches: int):
     _check(lib().quota_profile_begin(int(max_launches)), "quota_profile_begin")
 
 
+def quota_profile_bracket_ms(reps: int = 64):
+    """(cost of an event pair with no kernel in it, what one empty kernel adds), both in ms."""
+    bracket, empty = C.c_float(0.0), C.c_float(0.0)
+    _check(lib().quota_profile_bracket_ms(int(reps), _stream(), C.byref(bracket), C.byref(empty)),
+           "quota_profile_bracket_ms")
+    return bracket.value, empty.value
+
+
 def quota_profile_collect():
     """Returns {kernel name: dict(launches, total_ms, ops, bytes)} for the kernels that ran."""
     arr = (KernelStat * KERNEL_COUNT)()
@@ -229,3 +237,11 @@ def quota_profile_collect():
             out[lib().quota_kernel_name(i).decode()] = dict(launches=arr[i].launches, total_ms=arr[i].total_ms,
                                                             ops=arr[i].ops, bytes=arr[i].bytes)
     return out
+
+
+def quota_kernel_name(kernel_id: int) -> str:
+    return lib().quota_kernel_name(int(kernel_id)).decode()
+
+
+def quota_strerror(code: int) -> str:
+    return lib().quota_strerror(int(code)).decode()

@@ -381,5 +381,5 @@ extern "C" int quota_w4a4_gemm(const uint8_t *qa, const float *sa, int M, const 
     if (mt32 * nt128 > 256)
         return launch<1, 1, 4, 4, true, false>(QUOTA_K_GEMM_32X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
     // at most one workgroup per CU: a deeper weight prefetch is all that hides HBM latency
-    return launch<1, 1, 8, 4, true, false>(QUOTA_K_GEMM_32X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    return launch<1, 1, 8, 4, true, false>(QUOTA_K_GEMM_32X128_DEEP, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
 }

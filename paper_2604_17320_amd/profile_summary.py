@@ -1,0 +1,127 @@
+#!/usr/bin/env python3
+"""Condenses rocprofv3 CSV output of bench.py into the short text/JSON summaries kept under
+profiles/.
+
+    python -m paper_2604_17320_amd.profile_summary stats  <kernel_stats.csv>  [bench.json]
+    python -m paper_2604_17320_amd.profile_summary traffic <fetch_counter_collection.csv> \
+           <write_counter_collection.csv> <copy MiB> [bench.json]
+
+`stats` prints the per-kernel table of a `--kernel-trace --stats` run next to bench.py's own
+event-timed averages.  `traffic` turns two `--pmc` passes (FETCH_SIZE, then WRITE_SIZE, KiB per
+dispatch) into HBM bytes per launch for each library kernel; both counters are scaled by what
+they read for the plain elementwise copy of known size that bench.py ran in the same process
+(`--calibration-copy-mib`), and the JSON goes to stdout.
+"""
+import collections
+import csv
+import json
+import re
+import sys
+
+# profiler kernel name (substring) -> kernel class name used by the library's own timing
+CLASSES = [
+    ("w4a4_gemm_kernelILi2ELi2E", "w4a4_gemm_64x256"),
+    ("w4a4_gemm_kernelILi2ELi1ELi4ELi2ELb1ELb0E", "w4a4_gemm_64x128"),
+    ("w4a4_gemm_kernelILi1ELi1ELi4E", "w4a4_gemm_32x128"),
+    ("w4a4_gemm_kernelILi1ELi1ELi8E", "w4a4_gemm_32x128_deep"),
+    ("w4a4_gemm_kernel", "w4a4_gemm_other"),
+    ("silu_mul_quantize_act_kernel", "silu_mul_quantize_act"),
+    ("rmsnorm_quantize_act_kernel", "rmsnorm_quantize_act"),
+    ("quantize_act_kernel", "quantize_act"),
+    ("rope_kv_quant_kernel", "rope_kv_quant"),
+    ("kv_quant_append_kernel", "kv_quant_append"),
+    ("attn_fwd_kernel", "attention_fwd"),
+    ("colmass_reduce_kernel", "attention_colmass_reduce"),
+    ("colmass_kernel", "attention_colmass"),
+    ("score_topk_kernel", "score_tokens"),
+    ("topk_kernel", "topk_prune"),
+    ("compact_rows_kernel", "compact_rows"),
+    ("quantize_weights_kernel", "quantize_weights"),
+    ("pack_weights_kernel", "pack_weights"),
+]
+
+
+def classify(name):
+    for key, cls in CLASSES:
+        if key in name:
+            return cls
+    return None
+
+
+def load_bench(path):
+    if not path:
+        return None
+    with open(path) as f:
+        lines = [l for l in f.read().splitlines() if l.startswith("{")]
+    return json.loads(lines[-1]) if lines else None
+
+
+def stats(csv_path, bench_path=None):
+    bench = load_bench(bench_path)
+    agg = collections.OrderedDict()
+    for r in csv.DictReader(open(csv_path)):
+        cls = classify(r["Name"])
+        if cls is None:
+            continue
+        a = agg.setdefault(cls, [0, 0.0])
+        a[0] += int(r["Calls"])
+        a[1] += float(r["TotalDurationNs"])
+    total = sum(a[1] for a in agg.values())
+    print(f"{'kernel':28s} {'calls':>7s} {'avg us (trace)':>15s} {'share':>7s} {'avg us (events, bench.py)':>27s}")
+    for cls, (calls, ns) in sorted(agg.items(), key=lambda kv: -kv[1][1]):
+        ev = bench and bench["kernels"].get(cls, {}).get("avg_us")
+        print(f"{cls:28s} {calls:7d} {ns / calls / 1e3:15.2f} {100 * ns / total:6.1f}% "
+              f"{'' if ev is None else format(ev, '27.2f')}")
+    if bench:
+        print(f"\nbench.py line of the same run: {bench['value']} {bench['unit']}, {bench['ms_per_step']} ms/step, "
+              f"roofline {json.dumps(bench['roofline'])}")
+
+
+def per_kernel(csv_path, counter):
+    """{class: [values per dispatch]} plus the copy kernel's values."""
+    vals, copy = collections.defaultdict(list), []
+    for r in csv.DictReader(open(csv_path)):
+        if r["Counter_Name"] != counter:
+            continue
+        name, v = r["Kernel_Name"], float(r["Counter_Value"])
+        cls = classify(name)
+        if cls:
+            vals[cls].append(v)
+        elif "elementwise_kernel" in name and "AUnaryFunctor" in name:
+            copy.append((int(r["Grid_Size"]), v))      # torch.mul(src, 1.0, out=dst), 4 floats per thread
+    return vals, copy
+
+
+def traffic(fetch_csv, write_csv, copy_mib, bench_path=None):
+    bench = load_bench(bench_path)
+    copy_bytes = int(copy_mib) << 20
+    out = dict(counters="FETCH_SIZE, WRITE_SIZE (KiB per dispatch), one rocprofv3 --pmc pass each",
+               calibration={}, kernels={})
+    scale = {}
+    for tag, path, ctr in (("fetch", fetch_csv, "FETCH_SIZE"), ("write", write_csv, "WRITE_SIZE")):
+        vals, copy = per_kernel(path, ctr)
+        big = [v for g, v in copy if g == copy_bytes // 16]          # the copy itself, by its grid size
+        if len(big) != 1:
+            raise SystemExit(f"expected one calibration copy in {path}, found {len(big)}")
+        read_kib = big[0]
+        scale[tag] = copy_bytes / (read_kib * 1024.0)
+        out["calibration"][tag] = dict(copy_bytes=copy_bytes, counter_kib=read_kib, scale=round(scale[tag], 4))
+        for cls, v in vals.items():
+            rec = out["kernels"].setdefault(cls, {})
+            rec[f"{tag}_bytes"] = round(sum(v) / len(v) * 1024.0 * scale[tag])
+            rec[f"{tag}_dispatches"] = len(v)
+    if bench:
+        for cls, rec in out["kernels"].items():
+            k = bench["kernels"].get(cls)
+            if k and k.get("GBps") and k.get("avg_us"):
+                rec["algorithmic_bytes"] = round(k["GBps"] * 1e9 * k["avg_us"] * 1e-6)
+    print(json.dumps(out, indent=1))
+
+
+if __name__ == "__main__":
+    if len(sys.argv) >= 3 and sys.argv[1] == "stats":
+        stats(*sys.argv[2:4])
+    elif len(sys.argv) >= 5 and sys.argv[1] == "traffic":
+        traffic(*sys.argv[2:6])
+    else:
+        raise SystemExit(__doc__)
