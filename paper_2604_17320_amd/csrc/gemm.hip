@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
     constexpr bool CHUNK = CH > 0;
     constexpr int CHN = CHUNK ? CH : 1;
     static_assert(DEPTH % CHN == 0, "DEPTH must be a multiple of CH");
-    constexpr int LDS_A = 2 * CHN * ASTAGE, LDS_C = 4 * 32 * CROW / 8;     // in uint4
+    constexpr int LDS_A = (PIPE ? 3 : 2) * CHN * ASTAGE, LDS_C = 4 * 32 * CROW / 8;     // in uint4
     __shared__ uint4 lds_raw[LDS_A > LDS_C ? LDS_A : LDS_C];
 
     const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
@@ -214,43 +214,57 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
 
     const int Gpad = (G + DEPTH - 1) / DEPTH * DEPTH;
     if constexpr (PIPE) {
-        // Group-level software pipeline for the narrow tiles, where a SIMD holds a single
-        // wave and nothing else hides latency: while the MFMAs of group g run, the weights
-        // of group g+1 are unpacked and its activation fragments are already on their way
-        // from LDS.  Scheduling barriers pin the three phases of an iteration; without them
-        // the fragment reads sink next to their first use and every MFMA waits on LDS.
+        // Group-level software pipeline for the narrow tiles, where little else hides
+        // latency: while the MFMAs of group g run, the weights of group g+1 are unpacked,
+        // its activation fragments are already on their way from LDS, and (in the last
+        // group of a chunk) the activations two chunks ahead are unpacked into LDS.
+        // Three LDS buffers make that possible with one barrier per chunk: the buffer
+        // written at the end of chunk c is read from chunk c+2 on, so the fragment reads
+        // for the first group of chunk c+1 are issued before the barrier, not after it.
+        // Scheduling barriers pin the phases of an iteration; without them the fragment
+        // reads sink next to their first use and every MFMA waits on LDS.
         static_assert(CHUNK && DEPTH % 2 == 0, "PIPE needs chunked staging and an even DEPTH");
         i32x4 fbp[2][TN][4], fap[2][TM][4];
         float swp[2][TN];
+        uint4 *b0 = lds_raw, *b1 = lds_raw + CHN * ASTAGE, *b2 = lds_raw + 2 * CHN * ASTAGE;
+#pragma unroll
+        for (int c = 0; c < CHN; ++c) load_a(c, CHN + c);
+#pragma unroll
+        for (int c = 0; c < CHN; ++c) store_a(c, b1 + c * ASTAGE);
+        __syncthreads();
         unpack_w(0, 0, fbp[0], swp[0]);
-        read_a(lds_raw, fap[0]);
+        read_a(b0, fap[0]);
 #pragma unroll 1
         for (int g0 = 0; g0 < Gpad; g0 += DEPTH) {
 #pragma unroll
             for (int s = 0; s < DEPTH; ++s) {
                 const int g = g0 + s, cur = s & 1, nxt = cur ^ 1, s1 = (s + 1) % DEPTH;
                 const bool chunk_end = s % CHN == CHN - 1;
-                if (s % CHN == 0) {             // activations of the next CH groups -> registers
+                if (s % CHN == 0) {             // activations two chunks ahead -> registers
 #pragma unroll
-                    for (int c = 0; c < CHN; ++c) load_a(c, g + CHN + c);
+                    for (int c = 0; c < CHN; ++c) load_a(c, g + 2 * CHN + c);
                 }
                 load_w(s, g + DEPTH);           // stage s was unpacked during the previous group
-                if (!chunk_end) read_a(lds_raw + (cb * CHN + s % CHN + 1) * ASTAGE, fap[nxt]);
+                read_a(chunk_end ? b1 : b0 + (s % CHN + 1) * ASTAGE, fap[nxt]);
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_group(fap[cur], fbp[cur], swp[cur], g);
                 unpack_w(s1, g + 1, fbp[nxt], swp[nxt]);
+                if (chunk_end) {
+#pragma unroll
+                    for (int c = 0; c < CHN; ++c) store_a(c, b2 + c * ASTAGE);
+                }
+                constexpr int VPM = (ACC_OUT ? 12 : 8) + 6 / TM;     // VALU per MFMA slot
+                constexpr int VPM_END = VPM + 3 * CHN * LA / T;      // ... with the activation unpack
 #pragma unroll
                 for (int q = 0; q < 4 * T; ++q) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, (ACC_OUT ? 12 : 8) + 6 / TM, 0);
+                    if (chunk_end) __builtin_amdgcn_sched_group_barrier(0x002, VPM_END, 0);
+                    else __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                if (chunk_end) {                // next CH groups of activations -> the other half
-#pragma unroll
-                    for (int c = 0; c < CHN; ++c) store_a(c, lds_raw + ((cb ^ 1) * CHN + c) * ASTAGE);
+                if (chunk_end) {
                     __syncthreads();
-                    cb ^= 1;
-                    read_a(lds_raw + cb * CHN * ASTAGE, fap[nxt]);
+                    uint4 *t = b0; b0 = b1; b1 = b2; b2 = t;
                 }
             }
         }
