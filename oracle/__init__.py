@@ -203,4 +203,5 @@ def budget(r: float, V0: int) -> int:
     return int(math.ceil(Fraction(str(r)) * V0))
 
 
-from .layer import prefill_layer, LayerWeights  # noqa: E402,F401
+from .layer import (prefill_layer, decode_layer, decode_attention, dequant_kv, cache_from_prefill,  # noqa: E402,F401
+                    LayerWeights)

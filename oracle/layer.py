@@ -119,3 +119,88 @@ def prefill_layer(W: LayerWeights, x, pos, B, N, vis_begin, Nv, K, cos, sin,
     out.update(cache_kc=kc[flat], cache_ks=ks[flat], cache_vc=vc[flat], cache_vs=vs[flat])
     out["Nv_next"] = keep_idx.shape[1]
     return out
+
+
+def dequant_kv(codes, scales, g: int = 64):
+    """x_hat = fp16(code * scale): what attention sees of a 4-bit K or V row.
+
+    codes int8 [..., D] in [-8, 7]; scales fp16 [..., D/g].  The product of a
+    4-bit integer and an fp16 value is exact in fp32, so the only rounding is
+    the one back to fp16 -- the same value the quantizer reports as x_hat.
+    """
+    s = np.repeat(np.asarray(scales, np.float16).astype(np.float32), g, axis=-1)
+    return (np.asarray(codes, np.int8).astype(np.float32) * s).astype(np.float16)
+
+
+def decode_attention(q, kc, ks, vc, vs, H: int, dh: int):
+    """Single-query attention of one new token per sequence over its 4-bit cache.
+
+    q fp16 [B, H*dh] (rotated); kc/vc int8 [B, L, H*dh]; ks/vs fp16 [B, L, H*dh/64];
+    the L cached rows include the new token's own K/V (appended before the read).
+    Per head: s_t = q . k_hat_t / sqrt(dh), p = softmax_t(s), o = sum_t p_t v_hat_t,
+    all in fp64, o rounded once to fp16.  (Decode stage of the deployment pipeline:
+    attention over the pruned quantized KV cache.)
+    """
+    from . import f64_to_f16
+    B, L, D = kc.shape
+    khat = dequant_kv(kc, ks).astype(np.float64).reshape(B, L, H, dh)
+    vhat = dequant_kv(vc, vs).astype(np.float64).reshape(B, L, H, dh)
+    qf = np.asarray(q, np.float16).astype(np.float64).reshape(B, H, dh)
+    o = np.zeros((B, H, dh), np.float64)
+    for b in range(B):
+        for h in range(H):
+            s = khat[b, :, h, :] @ qf[b, h] / np.sqrt(float(dh))
+            p = np.exp(s - s.max())
+            p /= p.sum()
+            o[b, h] = p @ vhat[b, :, h, :]
+    return f64_to_f16(o.reshape(B, H * dh))
+
+
+def decode_layer(W: LayerWeights, x, pos, cache, cos, sin, inject=None):
+    """One decode step of one layer: a single new token per sequence.
+
+    x fp16 [B, d]; pos int32 [B] (the new token's original position id); cache: dict
+    with kc/vc int8 [B, L, d] and ks/vs fp16 [B, L, d/64] -- the layer's pruned
+    4-bit KV cache (kept prefill rows, then earlier decode tokens).  The new
+    token's K (post-RoPE) and V are quantized exactly like prefill rows, appended,
+    and attention reads the L+1 rows back from their 4-bit form.  Nothing is
+    pruned at decode time.  ``inject`` may override 'o' and 'z' (tests only).
+    Returns the step's tensors and the grown cache under 'cache'.
+    """
+    from . import quantize_act, rmsnorm, w4a4_gemm, rope, kv_quant, silu_mul
+    d = W.H * W.dh
+    x = np.ascontiguousarray(x, np.float16).reshape(-1, d)
+    B = x.shape[0]
+    pos = np.ascontiguousarray(pos, np.int32).reshape(B)
+    h1 = rmsnorm(x, W.gamma1, W.eps)
+    qa1, sa1, _, _ = quantize_act(h1)
+    qkv = w4a4_gemm(qa1, sa1, *W.qkv)
+    q = rope(qkv[:, :d], W.H, W.dh, pos, cos, sin)
+    k = rope(qkv[:, d:2 * d], W.H, W.dh, pos, cos, sin)
+    v = np.ascontiguousarray(qkv[:, 2 * d:])
+    kc, ks, _ = kv_quant(k)
+    vc, vs, _ = kv_quant(v)
+    grown = dict(kc=np.concatenate([cache["kc"], kc[:, None, :]], axis=1),
+                 ks=np.concatenate([cache["ks"], ks[:, None, :]], axis=1),
+                 vc=np.concatenate([cache["vc"], vc[:, None, :]], axis=1),
+                 vs=np.concatenate([cache["vs"], vs[:, None, :]], axis=1))
+    o = decode_attention(q, grown["kc"], grown["ks"], grown["vc"], grown["vs"], W.H, W.dh)
+    if inject and "o" in inject:
+        o = inject["o"]
+    qa2, sa2, _, _ = quantize_act(o)
+    x1 = w4a4_gemm(qa2, sa2, *W.o, residual=x)
+    h2 = rmsnorm(x1, W.gamma2, W.eps)
+    qa3, sa3, _, _ = quantize_act(h2)
+    gu = w4a4_gemm(qa3, sa3, *W.gu)
+    z = silu_mul(gu, W.F)
+    if inject and "z" in inject:
+        z = inject["z"]
+    qa4, sa4, _, _ = quantize_act(z)
+    x_next = w4a4_gemm(qa4, sa4, *W.down, residual=x1)
+    return dict(qkv=qkv, q=q, kc=kc, ks=ks, vc=vc, vs=vs, o=o, x1=x1, gu=gu, z=z, x_next=x_next,
+                cache=grown)
+
+
+def cache_from_prefill(out, B):
+    """The [B, L, .] cache arrays that a prefill_layer result appended."""
+    return {k: out["cache_" + k].reshape(B, -1, out["cache_" + k].shape[-1]) for k in ("kc", "ks", "vc", "vs")}

@@ -435,3 +435,75 @@ def test_layer_compaction_alignment():
     assert full["n_keep"] == N and np.array_equal(full["pos_next"], pos)
     none = oracle.prefill_layer(W, x, pos, B, N, 2, Nv, 0, cos, sin)
     assert none["n_keep"] == shape.Nt and none["Nv_next"] == 0
+
+
+# ---- decode over the pruned 4-bit KV cache --------------------------------------------------
+
+def test_dequant_kv_equals_the_quantizers_own_xhat():
+    x = (wl.rng(11, "kv").standard_normal((9, 256)) * 3).astype(np.float16)
+    codes, scales, xhat = oracle.kv_quant(x)
+    assert np.array_equal(oracle.dequant_kv(codes, scales), xhat)
+
+
+def test_decode_attention_closed_forms():
+    r = wl.rng(12, "dec")
+    B, H, dh = 2, 3, 64
+    q = r.standard_normal((B, H * dh)).astype(np.float16)
+    k = r.standard_normal((B * 5, H * dh)).astype(np.float16)
+    v = r.standard_normal((B * 5, H * dh)).astype(np.float16)
+    kc, ks, _ = oracle.kv_quant(k)
+    vc, vs, vhat = oracle.kv_quant(v)
+    sh = lambda a: a.reshape(B, 5, -1)
+    # a cache of one row: softmax over one key is 1, the output is that row's dequantized V
+    o1 = oracle.decode_attention(q, sh(kc)[:, :1], sh(ks)[:, :1], sh(vc)[:, :1], sh(vs)[:, :1], H, dh)
+    assert np.array_equal(o1, sh(vhat)[:, 0])
+    # identical keys: uniform probabilities, the output is the mean of the dequantized V rows
+    kc_same = np.repeat(sh(kc)[:, :1], 5, axis=1)
+    ks_same = np.repeat(sh(ks)[:, :1], 5, axis=1)
+    o2 = oracle.decode_attention(q, kc_same, ks_same, sh(vc), sh(vs), H, dh)
+    mean = sh(vhat).astype(np.float64).mean(axis=1)
+    assert np.allclose(o2.astype(np.float64), mean, rtol=0, atol=2e-3 * np.abs(mean).max())
+    assert np.max(np.abs(o2.astype(np.float64) - mean)) <= np.max(np.spacing(np.abs(mean).astype(np.float16))).astype(np.float64)
+    # a query of zeros gives uniform probabilities whatever the keys are
+    o3 = oracle.decode_attention(np.zeros_like(q), sh(kc), sh(ks), sh(vc), sh(vs), H, dh)
+    assert np.array_equal(o3, o2)
+
+
+def test_decode_step_equals_last_row_of_a_longer_prefill():
+    """Causality: with nothing pruned, the last token of an N-token prefill sees exactly what a decode
+    step sees that follows an (N-1)-token prefill -- same K/V codes, same attention row, same output."""
+    shape, W, x, pos, cos, sin = _small_layer(3)
+    B, N, Nv, d = shape.B, shape.N, shape.Nv, 128
+    full = oracle.prefill_layer(W, x, pos, B, N, 0, Nv, Nv, cos, sin)
+    xb, pb = x.reshape(B, N, d), pos.reshape(B, N)
+    head = oracle.prefill_layer(W, xb[:, :N - 1].reshape(-1, d), pb[:, :N - 1].reshape(-1), B, N - 1, 0, Nv, Nv,
+                                cos, sin)
+    cache = oracle.cache_from_prefill(head, B)
+    assert cache["kc"].shape == (B, N - 1, d)
+    dec = oracle.decode_layer(W, xb[:, N - 1], pb[:, N - 1], cache, cos, sin)
+    last = np.arange(B) * N + N - 1
+    assert np.array_equal(dec["kc"], full["kc"][last]) and np.array_equal(dec["vs"], full["vs"][last])
+    assert np.array_equal(dec["cache"]["kc"].reshape(B * N, d), full["cache_kc"])
+    for key in ("q", "o", "x1", "gu", "z", "x_next"):
+        assert np.array_equal(dec[key], full[key][last]), key
+
+
+def test_decode_reads_only_its_own_sequence_and_all_of_its_cache():
+    shape, W, x, pos, cos, sin = _small_layer(4)
+    B, N, Nv, d = shape.B, shape.N, shape.Nv, 128
+    head = oracle.prefill_layer(W, x, pos, B, N, 0, Nv, 5, cos, sin)       # pruned cache: 5 visual + text
+    cache = oracle.cache_from_prefill(head, B)
+    xn = wl.rng(4, "new").standard_normal((B, d)).astype(np.float16)
+    pn = np.full(B, N, np.int32)
+    cos, sin = wl.rope_tables(64, N + 1)
+    a = oracle.decode_layer(W, xn, pn, cache, cos, sin)
+    assert a["cache"]["kc"].shape[1] == 5 + shape.Nt + 1
+    # changing sequence 1's cache leaves sequence 0 untouched
+    c2 = {k: v.copy() for k, v in cache.items()}
+    c2["vc"][1] = -c2["vc"][1].clip(-7, 7)
+    b = oracle.decode_layer(W, xn, pn, c2, cos, sin)
+    assert np.array_equal(a["x_next"][0], b["x_next"][0]) and not np.array_equal(a["o"][1], b["o"][1])
+    # dropping a cached row changes the output of that sequence (every row is read)
+    c3 = {k: v[:, 1:] for k, v in cache.items()}
+    c = oracle.decode_layer(W, xn, pn, c3, cos, sin)
+    assert not np.array_equal(a["o"], c["o"])
