@@ -287,6 +287,34 @@ int quota_prefill_layer(const quota_layer *L, quota_state *st, int K_l,
                         const quota_score_params *p, quota_kv_cache *cache,
                         const quota_taps *taps_opt, void *ws, void *stream);
 
+/* ---- decode over the pruned 4-bit KV cache ------------------------------- */
+
+/* Single-query attention of one new token per sequence over `cache` (deployment
+ * pipeline: decoding reads the quantized KV cache that holds retained tokens
+ * only).  q fp16 [B][H*dh] (rotated); rows 0..len-1 of every sequence are read
+ * -- the new token's own K/V must already be appended -- as
+ * x_hat = fp16(code * scale); scores q.k_hat/sqrt(dh), fp32 softmax,
+ * o fp16 [B][H*dh].  B, H, dh, len come from the cache descriptor.
+ * Requires dh == 64 or 128 and 1 <= len <= 8192 (QUOTA_ERR_SHAPE beyond). */
+int quota_attention_decode(const void *q_f16, const quota_kv_cache *cache,
+                           void *o_f16, void *stream);
+
+size_t quota_decode_workspace_bytes(const quota_layer *L, int B);
+
+/* One decode step of one layer for one new token per sequence: RMSNorm +
+ * quantizer + W4A4 QKV, RoPE at the token's original position id pos[b], 4-bit
+ * quantization of its K/V exactly as for prefill rows, append at row
+ * cache->len (advanced by 1), attention over the whole cache, then the
+ * token-wise output projection and SwiGLU FFN.  Nothing is pruned at decode.
+ * x fp16 [B][d], pos int32 [B], x_out fp16 [B][d] (all device); B must equal
+ * cache->B.  taps_opt: qkv, q_rot, o, x1, gu, z dumps and inject_o / inject_z
+ * are honoured (parity harness).  ws: quota_decode_workspace_bytes bytes.
+ * QUOTA_ERR_CAPACITY when the cache is full (nothing is written). */
+int quota_decode_layer(const quota_layer *L, const void *x_f16,
+                       const int32_t *pos, int B, quota_kv_cache *cache,
+                       void *x_out_f16, const quota_taps *taps_opt, void *ws,
+                       void *stream);
+
 /* ---- per-kernel timing for benchmarks ----------------------------------- */
 
 /* Kernel classes the library launches.  The GEMM is split by tile shape
@@ -297,7 +325,7 @@ enum {
     QUOTA_K_GEMM_OTHER, QUOTA_K_ROPE_KV_QUANT,
     QUOTA_K_KV_QUANT_APPEND, QUOTA_K_ATTENTION_FWD, QUOTA_K_ATTENTION_COLMASS,
     QUOTA_K_SCORE_TOKENS, QUOTA_K_TOPK_PRUNE, QUOTA_K_COMPACT_ROWS, QUOTA_K_QUANTIZE_WEIGHTS,
-    QUOTA_K_PACK_WEIGHTS, QUOTA_KERNEL_COUNT
+    QUOTA_K_PACK_WEIGHTS, QUOTA_K_ATTENTION_DECODE, QUOTA_K_KV_APPEND_ROWS, QUOTA_KERNEL_COUNT
 };
 
 /* Per kernel class: launches seen, summed HIP-event time around them (ms) and

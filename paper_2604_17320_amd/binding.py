@@ -62,7 +62,7 @@ class KernelStat(C.Structure):
     _fields_ = [("launches", C.c_long), ("total_ms", C.c_double), ("ops", C.c_double), ("bytes", C.c_double)]
 
 
-KERNEL_COUNT = 17
+KERNEL_COUNT = 19
 
 _lib = None
 
@@ -78,7 +78,8 @@ def lib() -> C.CDLL:
         L.quota_strerror.restype = C.c_char_p
         L.quota_kernel_name.restype = C.c_char_p
         for name in ["quota_weights_packed_bytes", "quota_weights_scale_bytes",
-                     "quota_attention_workspace_bytes", "quota_prefill_workspace_bytes"]:
+                     "quota_attention_workspace_bytes", "quota_prefill_workspace_bytes",
+                     "quota_decode_workspace_bytes"]:
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -213,6 +214,22 @@ def quota_prefill_layer(L: Layer, st: State, K_l, p: ScoreParams, cache: KVCache
     _check(lib().quota_prefill_layer(C.byref(L), C.byref(st), int(K_l), C.byref(p), C.byref(cache),
                                      C.byref(taps) if taps is not None else None, _ptr(ws), _stream()),
            "quota_prefill_layer")
+
+
+def quota_attention_decode(q, cache: KVCache, o):
+    _check(lib().quota_attention_decode(_ptr(q, torch.float16), C.byref(cache), _ptr(o, torch.float16), _stream()),
+           "quota_attention_decode")
+
+
+def quota_decode_workspace_bytes(L: Layer, B):
+    return lib().quota_decode_workspace_bytes(C.byref(L), B)
+
+
+def quota_decode_layer(L: Layer, x, pos, B, cache: KVCache, x_out, taps, ws):
+    _check(lib().quota_decode_layer(C.byref(L), _ptr(x, torch.float16), _ptr(pos, torch.int32), int(B),
+                                    C.byref(cache), _ptr(x_out, torch.float16),
+                                    C.byref(taps) if taps is not None else None, _ptr(ws), _stream()),
+           "quota_decode_layer")
 
 
 def quota_profile_begin(max_launches: int):

@@ -1,0 +1,166 @@
+// Decode-side kernels: one new token per sequence attends over the layer's pruned
+// 4-bit KV cache (the cache that prefill wrote for retained tokens only), reading the
+// codes and group scales straight from HBM and dequantizing them in registers.
+// Bandwidth-bound by construction: a step moves H*dh + H*dh/16 bytes per cached token
+// and sequence (K and V codes plus fp16 scales), a quarter of an fp16 cache.
+#include "common.h"
+#include "internal.h"
+
+namespace {
+
+constexpr int DEC_LMAX = 8192;      // cached rows one workgroup can softmax over (scores live in LDS)
+
+// sign-extended code e (0..7) of a packed dword
+__device__ __forceinline__ float code_at(uint32_t w, int e)
+{
+    return (float)(((int)(w << (28 - 4 * e))) >> 28);
+}
+
+// Moves the B freshly quantized K/V rows (staged, dense) to row `len` of each sequence.
+__global__ __launch_bounds__(256) void kv_append_rows_kernel(
+    int d, const uint32_t *__restrict__ skc, const f16 *__restrict__ sks,
+    const uint32_t *__restrict__ svc, const f16 *__restrict__ svs, int capacity, int len,
+    uint32_t *__restrict__ ckc, f16 *__restrict__ cks, uint32_t *__restrict__ cvc,
+    f16 *__restrict__ cvs)
+{
+    const int b = blockIdx.x, n32 = d >> 3, ng = d >> 6;
+    const size_t crow = (size_t)b * capacity + len;
+    for (int i = threadIdx.x; i < n32; i += 256) {
+        ckc[crow * n32 + i] = skc[(size_t)b * n32 + i];
+        cvc[crow * n32 + i] = svc[(size_t)b * n32 + i];
+    }
+    for (int i = threadIdx.x; i < ng; i += 256) {
+        cks[crow * ng + i] = sks[(size_t)b * ng + i];
+        cvs[crow * ng + i] = svs[(size_t)b * ng + i];
+    }
+}
+
+// One workgroup per (head, sequence).  Pass 1: a thread per cached token computes
+// q . k_hat (k_hat = fp16(code * scale), the value the quantizer defines) and the scores
+// go to LDS; block max / sum; pass 2: DH/8 threads per token each own 8 channels of V and
+// accumulate p_t * v_hat_t over their share of the tokens; the token lanes are then summed
+// through LDS in a fixed order.
+template <int DH>
+__global__ __launch_bounds__(256) void decode_attention_kernel(
+    const f16 *__restrict__ q, int d, const uint32_t *__restrict__ kc, const f16 *__restrict__ ks,
+    const uint32_t *__restrict__ vc, const f16 *__restrict__ vs, int capacity, int L,
+    f16 *__restrict__ o)
+{
+    constexpr int WPT = DH / 8;             // packed dwords per token and head
+    constexpr int GPT = DH / 64;            // scale groups per token and head
+    constexpr int TL = 256 / WPT;           // token lanes of pass 2
+    __shared__ float qs[DH];
+    __shared__ float sc[DEC_LMAX];
+    __shared__ float red[TL * DH];
+    __shared__ float wred[8];
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int n32 = d >> 3, ng = d >> 6;
+    if (tid < DH) qs[tid] = (float)q[(size_t)b * d + h * DH + tid];
+    __syncthreads();
+    const float scale = 1.0f / sqrtf((float)DH);
+
+    float mx = -INFINITY;
+    for (int t = tid; t < L; t += 256) {
+        const size_t row = (size_t)b * capacity + t;
+        const uint32_t *kw = kc + row * n32 + h * WPT;
+        const f16 *sp = ks + row * ng + h * GPT;
+        float dot = 0.0f;
+#pragma unroll
+        for (int g = 0; g < GPT; ++g) {
+            const float s = (float)sp[g];
+#pragma unroll
+            for (int w4 = 0; w4 < 2; ++w4) {
+                const uint4 pk = *reinterpret_cast<const uint4 *>(kw + 8 * g + 4 * w4);
+                const uint32_t ww[4] = {pk.x, pk.y, pk.z, pk.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float kh = (float)(f16)(code_at(ww[i], e) * s);
+                        dot = fmaf(qs[64 * g + 32 * w4 + 8 * i + e], kh, dot);
+                    }
+            }
+        }
+        dot *= scale;
+        sc[t] = dot;
+        mx = fmaxf(mx, dot);
+    }
+    mx = wave_max(mx);
+    if ((tid & 63) == 0) wred[tid >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(wred[0], wred[1]), fmaxf(wred[2], wred[3]));
+    float sum = 0.0f;
+    for (int t = tid; t < L; t += 256) {
+        const float p = __expf(sc[t] - mx);
+        sc[t] = p;
+        sum += p;
+    }
+    sum = wave_sum(sum);
+    if ((tid & 63) == 0) wred[4 + (tid >> 6)] = sum;
+    __syncthreads();                        // also publishes every sc[t]
+    const float inv = 1.0f / (((wred[4] + wred[5]) + wred[6]) + wred[7]);
+
+    const int cl = tid % WPT, tl = tid / WPT;
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int t = tl; t < L; t += TL) {
+        const size_t row = (size_t)b * capacity + t;
+        const uint32_t w = vc[row * n32 + h * WPT + cl];
+        const float s = (float)vs[row * ng + h * GPT + (cl >> 3)];
+        const float p = sc[t];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = fmaf(p, (float)(f16)(code_at(w, e) * s), acc[e]);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[tl * DH + 8 * cl + e] = acc[e];
+    __syncthreads();
+    if (tid < DH) {
+        float v = 0.0f;
+#pragma unroll 4
+        for (int i = 0; i < TL; ++i) v += red[i * DH + tid];
+        o[(size_t)b * d + h * DH + tid] = (f16)(v * inv);
+    }
+}
+
+}  // namespace
+
+int quota_internal_kv_append_rows(int d, const uint8_t *skc, const void *sks, const uint8_t *svc,
+                                  const void *svs, quota_kv_cache *c, hipStream_t st)
+{
+    if (c->len + 1 > c->capacity) return QUOTA_ERR_CAPACITY;
+    ProfScope prof(QUOTA_K_KV_APPEND_ROWS, 0, 2.0 * c->B * (d + d / 16.0), st);
+    kv_append_rows_kernel<<<dim3(c->B), dim3(256), 0, st>>>(
+        d, (const uint32_t *)skc, (const f16 *)sks, (const uint32_t *)svc, (const f16 *)svs,
+        c->capacity, c->len, (uint32_t *)c->k_codes, (f16 *)c->k_scales, (uint32_t *)c->v_codes,
+        (f16 *)c->v_scales);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    c->len += 1;
+    return QUOTA_OK;
+}
+
+extern "C" int quota_attention_decode(const void *q_f16, const quota_kv_cache *cache, void *o_f16,
+                                      void *stream)
+{
+    if (!q_f16 || !cache || !o_f16 || !cache->k_codes || !cache->k_scales || !cache->v_codes ||
+        !cache->v_scales)
+        return QUOTA_ERR_NULL;
+    if (cache->B <= 0 || cache->H <= 0 || cache->len <= 0 || cache->len > cache->capacity)
+        return QUOTA_ERR_INVALID_ARG;
+    if ((cache->dh != 64 && cache->dh != 128) || cache->len > DEC_LMAX) return QUOTA_ERR_SHAPE;
+    const int d = cache->H * cache->dh;
+    hipStream_t st = (hipStream_t)stream;
+    const double rows = (double)cache->B * cache->len;
+    ProfScope prof(QUOTA_K_ATTENTION_DECODE, 4.0 * rows * d, rows * (d + d / 16.0) + 4.0 * cache->B * d, st);
+    dim3 grid(cache->H, cache->B), block(256);
+    if (cache->dh == 128)
+        decode_attention_kernel<128><<<grid, block, 0, st>>>(
+            (const f16 *)q_f16, d, (const uint32_t *)cache->k_codes, (const f16 *)cache->k_scales,
+            (const uint32_t *)cache->v_codes, (const f16 *)cache->v_scales, cache->capacity,
+            cache->len, (f16 *)o_f16);
+    else
+        decode_attention_kernel<64><<<grid, block, 0, st>>>(
+            (const f16 *)q_f16, d, (const uint32_t *)cache->k_codes, (const f16 *)cache->k_scales,
+            (const uint32_t *)cache->v_codes, (const f16 *)cache->v_scales, cache->capacity,
+            cache->len, (f16 *)o_f16);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    return QUOTA_OK;
+}

@@ -37,3 +37,8 @@ int quota_internal_compact(const quota_compact_args *a, hipStream_t st);
 
 int quota_internal_vector_metrics(const void *v_f16, int B, int Nv, int d, int ldv, long stride_b,
                                   float *sumsq, float *ressq, hipStream_t st);
+
+// Moves the B staged (dense) 4-bit K/V rows of a decode step to row cache->len of each
+// sequence and advances cache->len by 1.  QUOTA_ERR_CAPACITY if the cache is full.
+int quota_internal_kv_append_rows(int d, const uint8_t *skc, const void *sks, const uint8_t *svc,
+                                  const void *svs, quota_kv_cache *cache, hipStream_t st);

@@ -192,3 +192,55 @@ extern "C" int quota_prefill_layer(const quota_layer *L, quota_state *s, int K_l
     s->Nv = k_keep;
     return QUOTA_OK;
 }
+
+extern "C" size_t quota_decode_workspace_bytes(const quota_layer *L, int B)
+{
+    return quota_prefill_workspace_bytes(L, B, 1);
+}
+
+extern "C" int quota_decode_layer(const quota_layer *L, const void *x_f16, const int32_t *pos, int B,
+                                  quota_kv_cache *cache, void *x_out_f16, const quota_taps *taps,
+                                  void *ws, void *stream)
+{
+    if (!L || !x_f16 || !pos || !cache || !x_out_f16 || !ws || !L->gamma1 || !L->gamma2 || !L->cosT ||
+        !L->sinT)
+        return QUOTA_ERR_NULL;
+    const int H = L->H, dh = L->dh, F = L->F, d = H * dh;
+    if (B <= 0) return QUOTA_ERR_INVALID_ARG;
+    if ((dh != 64 && dh != 128) || F % 32 != 0) return QUOTA_ERR_SHAPE;
+    if (L->qkv.N != 3 * d || L->qkv.K != d || L->o.N != d || L->o.K != d || L->gu.N != 2 * F ||
+        L->gu.K != d || L->down.N != d || L->down.K != F)
+        return QUOTA_ERR_SHAPE;
+    if (cache->B != B || cache->H != H || cache->dh != dh) return QUOTA_ERR_SHAPE;
+    if (cache->len < 0) return QUOTA_ERR_INVALID_ARG;
+    if (cache->len + 1 > cache->capacity) return QUOTA_ERR_CAPACITY;
+
+    hipStream_t st = (hipStream_t)stream;
+    LayerWs w = carve(ws, B, 1, H, dh, F);
+    static const quota_taps no_taps = {};
+    const quota_taps *t = taps ? taps : &no_taps;
+
+    TRY(quota_rmsnorm_quantize_act(x_f16, B, d, d, L->gamma1, L->eps, w.qa, w.sa, nullptr, nullptr,
+                                   nullptr, st));
+    TRY(quota_w4a4_gemm(w.qa, w.sa, B, &L->qkv, w.qkv, 3 * d, nullptr, 0, nullptr, st));
+    TRY(dump(t->qkv, w.qkv, (size_t)B * 3 * d * 2, st));
+    TRY(quota_rope_kv_quant(w.qkv, B, H, dh, pos, L->cosT, L->sinT, L->n_pos, w.q_rot, w.khat, w.vhat,
+                            w.skc, w.sks, w.svc, w.svs, st));
+    TRY(dump(t->q_rot, w.q_rot, (size_t)B * d * 2, st));
+    // the new token's K/V join the cache first; attention then reads all of it in 4-bit form
+    TRY(quota_internal_kv_append_rows(d, w.skc, w.sks, w.svc, w.svs, cache, st));
+    TRY(quota_attention_decode(w.q_rot, cache, w.o, st));
+    TRY(dump(t->o, w.o, (size_t)B * d * 2, st));
+    const f16 *o_used = t->inject_o ? (const f16 *)t->inject_o : w.o;
+
+    TRY(quota_quantize_act(o_used, B, d, d, w.qa, w.sa, nullptr, nullptr, st));
+    TRY(quota_w4a4_gemm(w.qa, w.sa, B, &L->o, w.x1, d, x_f16, d, nullptr, st));
+    TRY(dump(t->x1, w.x1, (size_t)B * d * 2, st));
+    TRY(quota_rmsnorm_quantize_act(w.x1, B, d, d, L->gamma2, L->eps, w.qa, w.sa, nullptr, nullptr,
+                                   nullptr, st));
+    TRY(quota_w4a4_gemm(w.qa, w.sa, B, &L->gu, w.gu, 2 * F, nullptr, 0, nullptr, st));
+    TRY(dump(t->gu, w.gu, (size_t)B * 2 * F * 2, st));
+    TRY(quota_silu_mul_quantize_act(w.gu, B, F, w.qa, w.sa, t->z, t->inject_z, st));
+    TRY(quota_w4a4_gemm(w.qa, w.sa, B, &L->down, x_out_f16, d, w.x1, d, nullptr, st));
+    return QUOTA_OK;
+}

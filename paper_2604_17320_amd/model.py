@@ -87,6 +87,14 @@ class PrefillLayer:
     def workspace_bytes(self, B: int, N: int) -> int:
         return qb.quota_prefill_workspace_bytes(self.desc, B, N)
 
+    def decode_workspace_bytes(self, B: int) -> int:
+        return qb.quota_decode_workspace_bytes(self.desc, B)
+
+    def decode(self, x: torch.Tensor, pos: torch.Tensor, cache: "KVCache4", x_out: torch.Tensor,
+               ws: torch.Tensor, taps=None):
+        """One decode step of this layer: x fp16 [B, d], pos int32 [B]; appends to ``cache``."""
+        qb.quota_decode_layer(self.desc, x, pos, x.shape[0], cache.desc, x_out, taps, ws)
+
     def weight_bytes(self) -> int:
         return sum(w.nbytes() for w in (self.qkv, self.o, self.gu, self.down))
 
