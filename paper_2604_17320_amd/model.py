@@ -111,7 +111,7 @@ class PrefillStack:
     one KV cache per layer, one shared workspace.  ``run`` only enqueues."""
 
     def __init__(self, layers: List[PrefillLayer], B: int, N: int, vis_begin: int, Nv: int,
-                 budgets: List[int], params: Optional[qb.ScoreParams] = None):
+                 budgets: List[int], params: Optional[qb.ScoreParams] = None, decode_capacity: int = 0):
         assert len(budgets) == len(layers)
         self.layers, self.B, self.N0, self.vis_begin, self.Nv0 = layers, B, N, vis_begin, Nv
         self.budgets = list(budgets)
@@ -130,7 +130,12 @@ class PrefillStack:
             n = n - nv + k
             nv = k
             self.n_keep.append(n)
-            self.caches.append(KVCache4(B, n, L0.H, L0.dh))
+            self.caches.append(KVCache4(B, n + decode_capacity, L0.H, L0.dh))
+        self.dec_ws = None
+        if decode_capacity:
+            self.dec_ws = torch.empty(max(l.decode_workspace_bytes(B) for l in layers), dtype=torch.uint8,
+                                      device=dev)
+            self.dec_x = [torch.empty((B, L0.d), dtype=torch.float16, device=dev) for _ in range(2)]
 
     def run(self, x0: torch.Tensor, pos0: torch.Tensor, taps: Optional[List] = None):
         """x0 fp16 [B*N, d], pos0 int32 [B*N].  Returns (x_out view, pos_out view, N, Nv)."""
@@ -148,3 +153,16 @@ class PrefillStack:
             x_in, pos_in = x_out, pos_out
         d = self.layers[0].d
         return x_in[: B * N].view(B * N, d), pos_in[: B * N], N, Nv
+
+    def decode(self, x: torch.Tensor, pos: torch.Tensor, taps: Optional[List] = None):
+        """One decode step through every layer for one new token per sequence: x fp16 [B, d],
+        pos int32 [B] (original position ids).  Each layer appends the token's 4-bit K/V to its own
+        pruned cache and attends over it.  Returns the last layer's output (a view of an internal
+        buffer, valid until the next call)."""
+        assert self.dec_ws is not None, "construct the stack with decode_capacity > 0"
+        x_in = x
+        for i, L in enumerate(self.layers):
+            x_out = self.dec_x[i & 1]
+            L.decode(x_in, pos, self.caches[i], x_out, self.dec_ws, taps[i] if taps else None)
+            x_in = x_out
+        return x_in
