@@ -29,7 +29,9 @@ struct quota_compact_args {
     const void *x, *o;
     const int32_t *pos;
     const void *skc, *sks, *svc, *svs;     // staged 4-bit K/V of all N rows
-    void *x_out, *o_out;
+    void *x_out, *o_out;                   // o_out optional (fp16 copy of the kept attention rows)
+    uint8_t *oq_out;                       // optional: packed int4 codes of the kept attention rows ...
+    float *os_out;                         // ... and their per-token scales (the quantizer Q)
     int32_t *pos_out, *rows_out;
     quota_kv_cache *cache;
 };

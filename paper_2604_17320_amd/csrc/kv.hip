@@ -4,6 +4,7 @@
 // xor-shuffles and each lane stores one packed dword of 8 codes.
 #include "common.h"
 #include "internal.h"
+#include "rowquant.h"
 
 namespace {
 
@@ -125,13 +126,15 @@ __global__ __launch_bounds__(256) void kv_quant_append_kernel(
 }
 
 // Compaction gather of the layer (one workgroup per kept row): copies the
-// kept rows of the hidden state, the attention output and the positions, and
-// moves their staged 4-bit K/V rows into the layer's cache.
+// kept rows of the hidden state and the positions, moves their staged 4-bit
+// K/V rows into the layer's cache, and gathers the attention-output row --
+// copied (o_out) and/or quantized for the output projection (oq_out, os_out).
 __global__ __launch_bounds__(256) void compact_rows_kernel(
     int N, int vis_begin, int Nv, int k_keep, int n_keep, const int32_t *__restrict__ keep_idx,
     int d, const f16 *__restrict__ x, const f16 *__restrict__ o, const int32_t *__restrict__ pos,
     const uint32_t *__restrict__ skc, const f16 *__restrict__ sks, const uint32_t *__restrict__ svc,
     const f16 *__restrict__ svs, f16 *__restrict__ x_out, f16 *__restrict__ o_out,
+    uint32_t *__restrict__ oq_out, float *__restrict__ os_out,
     int32_t *__restrict__ pos_out, int32_t *__restrict__ rows_out, int capacity, int len,
     uint32_t *__restrict__ ckc, f16 *__restrict__ cks, uint32_t *__restrict__ cvc,
     f16 *__restrict__ cvs)
@@ -148,8 +151,29 @@ __global__ __launch_bounds__(256) void compact_rows_kernel(
     const uint4 *xs = reinterpret_cast<const uint4 *>(x + srow * d);
     const uint4 *os = reinterpret_cast<const uint4 *>(o + srow * d);
     uint4 *xd = reinterpret_cast<uint4 *>(x_out + drow * d);
-    uint4 *od = reinterpret_cast<uint4 *>(o_out + drow * d);
-    for (int i = threadIdx.x; i < n16; i += 256) { xd[i] = xs[i]; od[i] = os[i]; }
+    // the attention-output row is cached: it is copied and/or fed to the activation quantizer
+    // in front of the output projection (same code path as the stand-alone quantizer)
+    __shared__ double sm[12];
+    Pack16 v[ROW_MAXCHUNK];
+    float a = 0.0f;
+#pragma unroll
+    for (int r = 0; r < ROW_MAXCHUNK; ++r) {
+        int i = threadIdx.x + ROW_THREADS * r;
+        if (i < n16) {
+            xd[i] = xs[i];
+            v[r].u = os[i];
+            if (o_out) reinterpret_cast<uint4 *>(o_out + drow * d)[i] = v[r].u;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf((float)v[r].h[e]));
+        }
+    }
+    if (oq_out) {
+        double z0 = 0.0, z1 = 0.0;
+        block_max_sum2<4>(a, z0, z1, sm);
+        float s;
+        quantize_cached_row<false>(v, n16, a, oq_out + drow * n16, s);
+        if (threadIdx.x == 0) os_out[drow] = s;
+    }
     for (int i = threadIdx.x; i < n16; i += 256) {          // d/8 dwords of codes per row
         ckc[crow * n16 + i] = skc[srow * n16 + i];
         cvc[crow * n16 + i] = svc[srow * n16 + i];
@@ -171,13 +195,14 @@ int quota_internal_compact(const quota_compact_args *a, hipStream_t st)
 {
     quota_kv_cache *c = a->cache;
     if (c->len + a->n_keep > c->capacity) return QUOTA_ERR_CAPACITY;
+    if (a->d % 8 != 0 || a->d > ROW_MAXCHUNK * ROW_THREADS * 8) return QUOTA_ERR_SHAPE;
     if (a->n_keep == 0) return QUOTA_OK;
     const double rows = (double)a->n_keep * a->B, dd = a->d;
     ProfScope prof(QUOTA_K_COMPACT_ROWS, 0, rows * (2 * (4 * dd + dd + dd / 16) + 8), st);
     compact_rows_kernel<<<dim3(a->n_keep, a->B), dim3(256), 0, st>>>(
         a->N, a->vis_begin, a->Nv, a->k_keep, a->n_keep, a->keep_idx, a->d, (const f16 *)a->x,
         (const f16 *)a->o, a->pos, (const uint32_t *)a->skc, (const f16 *)a->sks,
-        (const uint32_t *)a->svc, (const f16 *)a->svs, (f16 *)a->x_out, (f16 *)a->o_out, a->pos_out,
+        (const uint32_t *)a->svc, (const f16 *)a->svs, (f16 *)a->x_out, (f16 *)a->o_out, (uint32_t *)a->oq_out, a->os_out, a->pos_out,
         a->rows_out, c->capacity, c->len, (uint32_t *)c->k_codes, (f16 *)c->k_scales,
         (uint32_t *)c->v_codes, (f16 *)c->v_scales);
     QUOTA_RETURN_IF_LAUNCH_FAILED();

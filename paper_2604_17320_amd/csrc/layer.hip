@@ -28,7 +28,7 @@ struct LayerWs {
     f16 *sks, *svs;
     float *sumsq, *ressq, *cm_inter, *cm_intra, *score;
     int32_t *keep_idx, *rows;
-    f16 *x_keep, *o_keep, *x1, *gu;
+    f16 *x_keep, *x1, *gu;
     void *attn_ws;
     size_t bytes;
 };
@@ -58,7 +58,6 @@ LayerWs carve(void *ws, int B, int N, int H, int dh, int F)
     w.keep_idx = c.take<int32_t>(M);
     w.rows = c.take<int32_t>(M);
     w.x_keep = c.take<f16>(M * d);
-    w.o_keep = c.take<f16>(M * d);
     w.x1 = c.take<f16>(M * d);
     w.gu = c.take<f16>(M * 2 * (size_t)F);
     w.attn_ws = c.take<char>(quota_attention_workspace_bytes(B, N, H, dh));
@@ -166,19 +165,20 @@ extern "C" int quota_prefill_layer(const quota_layer *L, quota_state *s, int K_l
         TRY(dump(t->keep_idx, w.keep_idx, (size_t)B * k_keep * 4, st));
     }
 
-    // compaction: kept rows of x / o / pos move on, their 4-bit K/V go to the cache
+    // compaction: kept rows of x / pos move on, their 4-bit K/V go to the cache, and the kept
+    // attention-output rows leave the gather already quantized for the output projection
     quota_compact_args ca;
     ca.B = B; ca.N = N; ca.vis_begin = vb; ca.Nv = Nv; ca.k_keep = k_keep; ca.n_keep = n_keep;
     ca.d = d; ca.keep_idx = w.keep_idx; ca.x = s->x; ca.o = o_used; ca.pos = s->pos;
     ca.skc = w.skc; ca.sks = w.sks; ca.svc = w.svc; ca.svs = w.svs;
-    ca.x_out = w.x_keep; ca.o_out = w.o_keep; ca.pos_out = s->pos_out; ca.rows_out = w.rows;
+    ca.x_out = w.x_keep; ca.o_out = nullptr; ca.oq_out = w.qa; ca.os_out = w.sa;
+    ca.pos_out = s->pos_out; ca.rows_out = w.rows;
     ca.cache = cache;
     TRY(quota_internal_compact(&ca, st));
     TRY(dump(t->rows, w.rows, (size_t)Mk * 4, st));
 
     // token-wise rest of the block on the kept rows only
     if (Mk > 0) {
-        TRY(quota_quantize_act(w.o_keep, Mk, d, d, w.qa, w.sa, nullptr, nullptr, st));
         TRY(quota_w4a4_gemm(w.qa, w.sa, Mk, &L->o, w.x1, d, w.x_keep, d, nullptr, st));
         TRY(dump(t->x1, w.x1, (size_t)Mk * d * 2, st));
         TRY(quota_rmsnorm_quantize_act(w.x1, Mk, d, d, L->gamma2, L->eps, w.qa, w.sa, nullptr,
