@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
     constexpr bool CHUNK = CH > 0;
     constexpr int CHN = CHUNK ? CH : 1;
     static_assert(DEPTH % CHN == 0, "DEPTH must be a multiple of CH");
-    constexpr int LDS_A = (PIPE ? 3 : 2) * CHN * ASTAGE, LDS_C = 4 * 32 * CROW / 8;     // in uint4
+    constexpr int LDS_A = 2 * CHN * ASTAGE, LDS_C = 4 * 32 * CROW / 8;     // in uint4
     __shared__ uint4 lds_raw[LDS_A > LDS_C ? LDS_A : LDS_C];
 
     const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
@@ -215,56 +215,42 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
     const int Gpad = (G + DEPTH - 1) / DEPTH * DEPTH;
     if constexpr (PIPE) {
         // Group-level software pipeline for the narrow tiles, where little else hides
-        // latency: while the MFMAs of group g run, the weights of group g+1 are unpacked,
-        // its activation fragments are already on their way from LDS, and (in the last
-        // group of a chunk) the activations two chunks ahead are unpacked into LDS.
-        // Three LDS buffers make that possible with one barrier per chunk: the buffer
-        // written at the end of chunk c is read from chunk c+2 on, so the fragment reads
-        // for the first group of chunk c+1 are issued before the barrier, not after it.
-        // Scheduling barriers pin the phases of an iteration; without them the fragment
-        // reads sink next to their first use and every MFMA waits on LDS.
+        // latency: while the MFMAs of group g run, the weights of group g+1 are unpacked and
+        // its activation fragments are already on their way from LDS.  Scheduling barriers
+        // pin the phases of an iteration; without them the fragment reads sink next to their
+        // first use and every MFMA waits on LDS.
         static_assert(CHUNK && DEPTH % 2 == 0, "PIPE needs chunked staging and an even DEPTH");
         i32x4 fbp[2][TN][4], fap[2][TM][4];
         float swp[2][TN];
-        uint4 *b0 = lds_raw, *b1 = lds_raw + CHN * ASTAGE, *b2 = lds_raw + 2 * CHN * ASTAGE;
-#pragma unroll
-        for (int c = 0; c < CHN; ++c) load_a(c, CHN + c);
-#pragma unroll
-        for (int c = 0; c < CHN; ++c) store_a(c, b1 + c * ASTAGE);
-        __syncthreads();
         unpack_w(0, 0, fbp[0], swp[0]);
-        read_a(b0, fap[0]);
+        read_a(lds_raw, fap[0]);
 #pragma unroll 1
         for (int g0 = 0; g0 < Gpad; g0 += DEPTH) {
 #pragma unroll
             for (int s = 0; s < DEPTH; ++s) {
                 const int g = g0 + s, cur = s & 1, nxt = cur ^ 1, s1 = (s + 1) % DEPTH;
                 const bool chunk_end = s % CHN == CHN - 1;
-                if (s % CHN == 0) {             // activations two chunks ahead -> registers
+                if (s % CHN == 0) {             // activations of the next CH groups -> registers
 #pragma unroll
-                    for (int c = 0; c < CHN; ++c) load_a(c, g + 2 * CHN + c);
+                    for (int c = 0; c < CHN; ++c) load_a(c, g + CHN + c);
                 }
                 load_w(s, g + DEPTH);           // stage s was unpacked during the previous group
-                read_a(chunk_end ? b1 : b0 + (s % CHN + 1) * ASTAGE, fap[nxt]);
+                if (!chunk_end) read_a(lds_raw + (cb * CHN + s % CHN + 1) * ASTAGE, fap[nxt]);
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_group(fap[cur], fbp[cur], swp[cur], g);
                 unpack_w(s1, g + 1, fbp[nxt], swp[nxt]);
-                if (chunk_end) {
-#pragma unroll
-                    for (int c = 0; c < CHN; ++c) store_a(c, b2 + c * ASTAGE);
-                }
-                constexpr int VPM = (ACC_OUT ? 12 : 8) + 6 / TM;     // VALU per MFMA slot
-                constexpr int VPM_END = VPM + 3 * CHN * LA / T;      // ... with the activation unpack
 #pragma unroll
                 for (int q = 0; q < 4 * T; ++q) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    if (chunk_end) __builtin_amdgcn_sched_group_barrier(0x002, VPM_END, 0);
-                    else __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, (ACC_OUT ? 12 : 8) + 6 / TM, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                if (chunk_end) {
+                if (chunk_end) {                // next CH groups of activations -> the other half
+#pragma unroll
+                    for (int c = 0; c < CHN; ++c) store_a(c, lds_raw + ((cb ^ 1) * CHN + c) * ASTAGE);
                     __syncthreads();
-                    uint4 *t = b0; b0 = b1; b1 = b2; b2 = t;
+                    cb ^= 1;
+                    read_a(lds_raw + cb * CHN * ASTAGE, fap[nxt]);
                 }
             }
         }
@@ -383,17 +369,34 @@ extern "C" int quota_w4a4_gemm(const uint8_t *qa, const float *sa, int M, const 
     const f16 *res = (const f16 *)residual_opt;
     if (acc_i32_opt)
         return launch<2, 1, 2, 0, false, true>(QUOTA_K_GEMM_OTHER, qa, sa, M, W, y, ldy, res, ldr, acc_i32_opt, st);
-    // Tile choice by how many workgroups a shape yields (2 fit on a CU): the wide tiles
-    // reuse each unpacked weight for 64 rows but need ~2 workgroups per CU to hide their
-    // latencies; below that the 32-row tiles spread the same work over more waves.
-    const long mt64 = (M + 63) / 64, mt32 = (M + 31) / 32;
-    const long nt256 = (W->N + 255) / 256, nt128 = (W->N + 127) / 128;
-    if (mt64 * nt256 >= 448)
-        return launch<2, 2, 3, 0, false, false>(QUOTA_K_GEMM_64X256, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
-    if (mt64 * nt128 >= 448)
-        return launch<2, 1, 4, 2, true, false>(QUOTA_K_GEMM_64X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
-    if (mt32 * nt128 > 256)
-        return launch<1, 1, 4, 4, true, false>(QUOTA_K_GEMM_32X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
-    // at most one workgroup per CU: a deeper weight prefetch is all that hides HBM latency
-    return launch<1, 1, 8, 4, true, false>(QUOTA_K_GEMM_32X128_DEEP, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    // Tile choice by a small cost model fitted to measured kernel times on this GPU (us).
+    // W workgroups run R at a time per CU on 256 CUs; a launch that fits (W <= 256 R) costs
+    // c0 + G * u[workgroups per CU - 1], a larger one c0 + G * u[R-1] * (f0 + f1 * W / (256 R)).
+    // Wide tiles reuse each unpacked weight for 64 rows but need full rounds; the 32-row tiles
+    // spread small problems over more waves; the deep variant prefetches weights 8 groups
+    // ahead for launches of at most one workgroup per CU.
+    struct Tile { int bm, bn, R; float c0, u[3], f0, f1; };
+    static const Tile tiles[4] = {
+        {64, 256, 2, 13.0f, {0.69f, 1.34f, 0.0f}, 0.0f, 1.22f},     // <2,2,3,0>
+        {64, 128, 2, 6.0f, {0.39f, 0.69f, 0.0f}, 0.0f, 1.27f},      // <2,1,4,2> pipelined
+        {32, 128, 3, 0.5f, {0.39f, 0.61f, 0.82f}, 0.35f, 0.92f},    // <1,1,4,2> pipelined
+        {32, 128, 2, 4.0f, {0.27f, 0.46f, 0.0f}, 0.0f, 1.45f},      // <1,1,8,4> pipelined, deep prefetch
+    };
+    const int G = (W->K + QUOTA_GROUP_W - 1) / QUOTA_GROUP_W;
+    int best = 0;
+    float best_t = 0.0f;
+    for (int i = 0; i < 4; ++i) {
+        const Tile &t = tiles[i];
+        const long wgs = (long)((M + t.bm - 1) / t.bm) * ((W->N + t.bn - 1) / t.bn);
+        const float x = (float)wgs / (256.0f * t.R);
+        const float est = x <= 1.0f ? t.c0 + G * t.u[(wgs + 255) / 256 - 1]
+                                    : t.c0 + G * t.u[t.R - 1] * (t.f0 + t.f1 * x);
+        if (i == 0 || est < best_t) { best = i; best_t = est; }
+    }
+    switch (best) {
+    case 0: return launch<2, 2, 3, 0, false, false>(QUOTA_K_GEMM_64X256, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    case 1: return launch<2, 1, 4, 2, true, false>(QUOTA_K_GEMM_64X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    case 2: return launch<1, 1, 4, 2, true, false>(QUOTA_K_GEMM_32X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    default: return launch<1, 1, 8, 4, true, false>(QUOTA_K_GEMM_32X128_DEEP, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    }
 }
