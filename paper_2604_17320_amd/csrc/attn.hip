@@ -5,7 +5,9 @@
 // per-lane scalar: S^T = K Q^T puts the query on the lane (column) and the
 // keys on the accumulator registers; the probabilities then feed
 // O^T += V^T P^T straight from those registers (their register->key mapping is
-// exactly the k-slot mapping of the B operand of v_mfma_f32_32x32x8_f16).
+// the k-slot mapping chosen for the B operand of v_mfma_f32_32x32x16_f16; a
+// contraction does not care which element sits in which k-slot as long as both
+// operands agree, so V^T is read with the same key-to-slot mapping).
 //
 // Pass 2 owns key columns instead: S = Q K^T puts the key on the lane, so the
 // column sums over queries are in-lane adds in a fixed order (deterministic,
@@ -19,8 +21,8 @@ constexpr int KT = 64;       // keys per tile (pass 1), queries per tile (pass 2
 
 template <int DH>
 struct AttnSmem {
-    f16 k[KT][DH + 4];       // row stride 2 banks apart: conflict-free 8-byte reads
-    f16 vt[DH][KT + 4];      // V transposed: [channel][key]
+    alignas(16) f16 k[KT][DH + 8];       // row stride = odd number of 16-byte units: conflict-free 16-byte reads
+    alignas(16) f16 vt[DH][KT + 4];      // V transposed: [channel][key]
 };
 
 template <int DH>
@@ -28,7 +30,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
     const f16 *__restrict__ q, const f16 *__restrict__ khat, const f16 *__restrict__ vhat, int N,
     int H, f16 *__restrict__ o, float *__restrict__ lse2, float scale_log2)
 {
-    constexpr int T = DH / 8;        // k-steps of the QK product
+    constexpr int T = DH / 16;       // k-steps (16 channels each) of the QK product
     constexpr int DB = DH / 32;      // 32-channel blocks of the output
     constexpr int CPR = DH / 8;      // 16-byte chunks per head row
     __shared__ AttnSmem<DH> sm;
@@ -38,13 +40,13 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
     const int qw0 = q0 + wave * 32, qi = qw0 + l32;       // this lane's query
     const size_t base = (size_t)b * N * d + (size_t)h * DH;
 
-    f16x4 qf[T];
+    f16x8 qf[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) {
         if (qi < N)
-            qf[t] = *reinterpret_cast<const f16x4 *>(q + base + (size_t)qi * d + 8 * t + 4 * hl);
+            qf[t] = *reinterpret_cast<const f16x8 *>(q + base + (size_t)qi * d + 16 * t + 8 * hl);
         else
-            qf[t] = f16x4{0, 0, 0, 0};
+            qf[t] = f16x8{0, 0, 0, 0, 0, 0, 0, 0};
     }
     f32x16 oacc[DB];
 #pragma unroll
@@ -75,14 +77,12 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
     fetch(0);
     for (int kt0 = 0; kt0 <= q_last_wg; kt0 += KT) {
         __syncthreads();
-        // K rows (8-byte stores) and V transposed (2-byte stores, lane = key)
+        // K rows (16-byte stores) and V transposed (2-byte stores, lane = key)
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
             const int i = tid + 256 * j;
             const int keyk = i / CPR, ck = i % CPR, keyv = i % KT, cv = i / KT;
-            uint2 *dst = reinterpret_cast<uint2 *>(&sm.k[keyk][8 * ck]);
-            dst[0] = make_uint2(rk[j].w[0], rk[j].w[1]);
-            dst[1] = make_uint2(rk[j].w[2], rk[j].w[3]);
+            *reinterpret_cast<uint4 *>(&sm.k[keyk][8 * ck]) = rk[j].u;
 #pragma unroll
             for (int e = 0; e < 8; ++e) sm.vt[8 * cv + e][keyv] = rv[j].h[e];
         }
@@ -97,8 +97,8 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
             for (int r = 0; r < 16; ++r) s[sb][r] = 0.0f;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
-                f16x4 kf = *reinterpret_cast<const f16x4 *>(&sm.k[32 * sb + l32][8 * t + 4 * hl]);
-                s[sb] = __builtin_amdgcn_mfma_f32_32x32x8f16(kf, qf[t], s[sb], 0, 0, 0);
+                f16x8 kf = *reinterpret_cast<const f16x8 *>(&sm.k[32 * sb + l32][16 * t + 8 * hl]);
+                s[sb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[t], s[sb], 0, 0, 0);
             }
         }
         float mx = -INFINITY;
@@ -117,15 +117,18 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
         float alpha = exp2f(m_run - m_new);
         m_run = m_new;
         float psum = 0.0f;
-        f16x4 pf[2][4];
+        // k-slot j of step u holds key 32 sb + 16 u + 8 (j / 4) + 4 hl + j % 4: registers 8u .. 8u+7
+        f16x8 pf[2][2];
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                float p0 = exp2f(s[sb][4 * u + 0] - m_new), p1 = exp2f(s[sb][4 * u + 1] - m_new);
-                float p2 = exp2f(s[sb][4 * u + 2] - m_new), p3 = exp2f(s[sb][4 * u + 3] - m_new);
-                psum += (p0 + p1) + (p2 + p3);
-                pf[sb][u] = f16x4{(f16)p0, (f16)p1, (f16)p2, (f16)p3};
+            for (int u = 0; u < 2; ++u) {
+                float p[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) p[j] = exp2f(s[sb][8 * u + j] - m_new);
+                psum += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+                pf[sb][u] = f16x8{(f16)p[0], (f16)p[1], (f16)p[2], (f16)p[3],
+                                  (f16)p[4], (f16)p[5], (f16)p[6], (f16)p[7]};
             }
         l_run = l_run * alpha + psum;
 #pragma unroll
@@ -135,10 +138,12 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
 #pragma unroll
             for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    f16x4 vf = *reinterpret_cast<const f16x4 *>(
-                        &sm.vt[32 * i + l32][32 * sb + 8 * u + 4 * hl]);
-                    oacc[i] = __builtin_amdgcn_mfma_f32_32x32x8f16(vf, pf[sb][u], oacc[i], 0, 0, 0);
+                for (int u = 0; u < 2; ++u) {
+                    const f16 *vrow = &sm.vt[32 * i + l32][32 * sb + 16 * u + 4 * hl];
+                    f16x4 v0 = *reinterpret_cast<const f16x4 *>(vrow);
+                    f16x4 v1 = *reinterpret_cast<const f16x4 *>(vrow + 8);
+                    f16x8 vf = f16x8{v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+                    oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[sb][u], oacc[i], 0, 0, 0);
                 }
         }
     }
@@ -159,7 +164,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
 
 template <int DH>
 struct CmSmem {
-    f16 q[KT][DH + 4];
+    alignas(16) f16 q[KT][DH + 8];
     float lse[KT];
 };
 
@@ -169,7 +174,7 @@ __global__ __launch_bounds__(256) void colmass_kernel(
     const f16 *__restrict__ q, const f16 *__restrict__ khat, const float *__restrict__ lse2, int N,
     int H, int vis_begin, int Nv, float *__restrict__ partial, float scale_log2)
 {
-    constexpr int T = DH / 8, CPR = DH / 8;
+    constexpr int T = DH / 16, CPR = DH / 8;
     __shared__ CmSmem<DH> sm;
     const int d = H * DH;
     const int b = blockIdx.z, h = blockIdx.y;
@@ -179,13 +184,13 @@ __global__ __launch_bounds__(256) void colmass_kernel(
     const bool key_ok = key < vis_begin + Nv;
     const size_t base = (size_t)b * N * d + (size_t)h * DH;
 
-    f16x4 kf[T];
+    f16x8 kf[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) {
         if (key_ok)
-            kf[t] = *reinterpret_cast<const f16x4 *>(khat + base + (size_t)key * d + 8 * t + 4 * hl);
+            kf[t] = *reinterpret_cast<const f16x8 *>(khat + base + (size_t)key * d + 16 * t + 8 * hl);
         else
-            kf[t] = f16x4{0, 0, 0, 0};
+            kf[t] = f16x8{0, 0, 0, 0, 0, 0, 0, 0};
     }
     float acc_txt = 0.0f, acc_vis = 0.0f;
     constexpr int PER = KT * CPR / 256;
@@ -208,9 +213,7 @@ __global__ __launch_bounds__(256) void colmass_kernel(
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
             const int i = tid + 256 * j, r = i / CPR, c = i % CPR;
-            uint2 *dst = reinterpret_cast<uint2 *>(&sm.q[r][8 * c]);
-            dst[0] = make_uint2(rq[j].w[0], rq[j].w[1]);
-            dst[1] = make_uint2(rq[j].w[2], rq[j].w[3]);
+            *reinterpret_cast<uint4 *>(&sm.q[r][8 * c]) = rq[j].u;
         }
         if (tid < KT) sm.lse[tid] = rl;
         __syncthreads();
@@ -223,8 +226,8 @@ __global__ __launch_bounds__(256) void colmass_kernel(
             for (int r = 0; r < 16; ++r) s[r] = 0.0f;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
-                f16x4 qf = *reinterpret_cast<const f16x4 *>(&sm.q[32 * sb + l32][8 * t + 4 * hl]);
-                s = __builtin_amdgcn_mfma_f32_32x32x8f16(qf, kf[t], s, 0, 0, 0);
+                f16x8 qf = *reinterpret_cast<const f16x8 *>(&sm.q[32 * sb + l32][16 * t + 8 * hl]);
+                s = __builtin_amdgcn_mfma_f32_32x32x16_f16(qf, kf[t], s, 0, 0, 0);
             }
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
