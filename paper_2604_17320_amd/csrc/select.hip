@@ -1,10 +1,10 @@
 // Token scoring (Eq. 6-8) and deterministic budgeted top-k (Eq. 9).
-// One 256-thread workgroup per sequence.  Order statistics and the top-k
-// threshold come from an exact 4-pass, 8-bit radix select on order-preserving
-// uint32 keys, run by ONE WAVE with a private 256-bin LDS histogram (integer
-// atomics, so the result does not depend on execution order; no workgroup
-// barrier inside the select).  The four metrics are normalised in parallel,
-// one wave each; the top-k runs on wave 0.
+// One workgroup per sequence.  Order statistics and the top-k threshold come
+// from an exact 4-pass, 8-bit radix select on order-preserving uint32 keys,
+// run by ONE WAVE with a private 256-bin LDS histogram (integer atomics, so
+// the result does not depend on execution order; no workgroup barrier inside
+// the select).  The eight percentile bounds of the four metrics are found in
+// parallel, one wave each; the top-k runs on wave 0.
 #include "common.h"
 #include "internal.h"
 
@@ -85,57 +85,78 @@ struct MetricSrc {
     size_t osq, ocm;        // offsets of this sequence in the sumsq/ressq and cm arrays
 };
 
-// Loads the four Eq. 6 metrics of sequence b into LDS as order-preserving keys
-// (all loads of a thread are independent, so one memory latency covers them),
-// then finds the percentile bounds (one wave per metric, keys in LDS), then
-// fuses the score of every token.  mk: 4*MAXV keys, hist: 4*256 ints, lohi: 8 floats.
+constexpr int SCORE_THREADS = 1024;
+
+// Loads the four Eq. 6 metrics of sequence b into LDS as order-preserving keys, finds the
+// eight percentile bounds (one wave per bound, keys in LDS), then fuses the score of every
+// token.  1024 threads: the load phase is one memory round trip deep -- a thread owns a
+// quarter of the heads of up to three tokens and issues all those loads back to back.
+// mk: 4*MAXV keys, hist: 8*256 ints, lohi: 8 floats.
 __device__ void score_phase(const MetricSrc &src, int B, int Nv, int b, const quota_score_params &p,
                             float *__restrict__ score, float *__restrict__ normed, uint32_t *mk,
                             int *hist, float *lohi)
 {
-    const int wave = threadIdx.x >> 6;
-    for (int i = threadIdx.x; i < Nv; i += 256) {
-        float m_inter, m_intra;
-        if (src.partial) {      // head mean in head order: (sum_h partial) * (1/H)
-            float st = 0.0f, sv = 0.0f;
-            const float2 *pp = reinterpret_cast<const float2 *>(src.partial) + (size_t)b * src.H * Nv + i;
-            for (int h0 = 0; h0 < src.H; h0 += 8) {        // 8 independent loads in flight, adds in head order
-                float2 v[8];
+    const int tid = threadIdx.x, wave = tid >> 6;
+    if (src.partial) {
+        // head mean: lane quarter hq sums heads [hq*H/4 .. ) in head order, the four partial
+        // sums are combined as (s0 + s1) + (s2 + s3), then * (1/H)
+        const int hq = tid & 3, hper = (src.H + 3) / 4, h_lo = hq * hper, h_hi = min(h_lo + hper, src.H);
+        const float2 *pp = reinterpret_cast<const float2 *>(src.partial) + (size_t)b * src.H * Nv;
+        const float invH = 1.0f / (float)src.H;
+        for (int i0 = 0; i0 < Nv; i0 += 3 * (SCORE_THREADS / 4)) {
+            float st[3] = {0.0f, 0.0f, 0.0f}, sv[3] = {0.0f, 0.0f, 0.0f};
+            for (int h0 = h_lo; h0 < h_hi; h0 += 8) {
+                float2 v[3][8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    v[u] = h0 + u < src.H ? pp[(size_t)(h0 + u) * Nv] : make_float2(0.0f, 0.0f);
+                for (int r = 0; r < 3; ++r) {
+                    const int i = i0 + (tid >> 2) + r * (SCORE_THREADS / 4);
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    if (h0 + u < src.H) { st += v[u].x; sv += v[u].y; }
+                    for (int u = 0; u < 8; ++u)
+                        v[r][u] = (i < Nv && h0 + u < h_hi) ? pp[(size_t)(h0 + u) * Nv + i] : make_float2(0.0f, 0.0f);
+                }
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) { st[r] += v[r][u].x; sv[r] += v[r][u].y; }
             }
-            const float invH = 1.0f / (float)src.H;
-            m_inter = st * invH;
-            m_intra = sv * invH;
-            if (src.cm_out_inter) src.cm_out_inter[src.ocm + i] = m_inter;
-            if (src.cm_out_intra) src.cm_out_intra[src.ocm + i] = m_intra;
-        } else {
-            m_inter = src.cm_inter[src.ocm + i];
-            m_intra = src.cm_intra[src.ocm + i];
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                const int i = i0 + (tid >> 2) + r * (SCORE_THREADS / 4);
+                float a = st[r], c = sv[r];
+                a += __shfl_xor(a, 1, 64); c += __shfl_xor(c, 1, 64);
+                a += __shfl_xor(a, 2, 64); c += __shfl_xor(c, 2, 64);
+                if (i < Nv && hq == 0) {
+                    const float m_inter = a * invH, m_intra = c * invH;
+                    if (src.cm_out_inter) src.cm_out_inter[src.ocm + i] = m_inter;
+                    if (src.cm_out_intra) src.cm_out_intra[src.ocm + i] = m_intra;
+                    mk[1 * MAXV + i] = float_key(m_inter);
+                    mk[2 * MAXV + i] = float_key(m_intra);
+                }
+            }
+        }
+    }
+    for (int i = tid; i < Nv; i += SCORE_THREADS) {
+        if (!src.partial) {
+            mk[1 * MAXV + i] = float_key(src.cm_inter[src.ocm + i]);
+            mk[2 * MAXV + i] = float_key(src.cm_intra[src.ocm + i]);
         }
         mk[0 * MAXV + i] = float_key(sqrtf(src.sumsq[src.osq + i]));    // m_mag
-        mk[1 * MAXV + i] = float_key(m_inter);
-        mk[2 * MAXV + i] = float_key(m_intra);
         mk[3 * MAXV + i] = float_key(sqrtf(src.ressq[src.osq + i]));    // m_res
     }
     __syncthreads();
     const int r_lo = (p.pct_lo * (Nv - 1) + 50) / 100, r_hi = (p.pct_hi * (Nv - 1) + 50) / 100;
-    {
-        const uint32_t *keys = mk + wave * MAXV;    // 4 waves <-> 4 metrics
+    if (wave < 8) {                                 // wave 2m: low bound of metric m, wave 2m+1: high bound
+        const uint32_t *keys = mk + (wave >> 1) * MAXV;
         auto key_at = [&](int i) { return keys[i]; };
-        uint32_t klo = wave_radix_select(key_at, Nv, r_lo, hist + 256 * wave);
-        uint32_t khi = wave_radix_select(key_at, Nv, r_hi, hist + 256 * wave);
-        if ((threadIdx.x & 63) == 0) { lohi[2 * wave] = key_float(klo); lohi[2 * wave + 1] = key_float(khi); }
+        uint32_t kb = wave_radix_select(key_at, Nv, (wave & 1) ? r_hi : r_lo, hist + 256 * wave);
+        if ((tid & 63) == 0) lohi[wave] = key_float(kb);
     }
     __syncthreads();
-    float sc[MAXV / 256];
+    constexpr int PER = MAXV / SCORE_THREADS;
+    float sc[PER];
 #pragma unroll
-    for (int r = 0; r < MAXV / 256; ++r) {
-        const int i = threadIdx.x + 256 * r;
+    for (int r = 0; r < PER; ++r) {
+        const int i = tid + SCORE_THREADS * r;
         if (i < Nv) {
             float g0 = robust_unit(key_float(mk[0 * MAXV + i]), lohi[0], lohi[1]);
             float g1 = robust_unit(key_float(mk[1 * MAXV + i]), lohi[2], lohi[3]);
@@ -162,8 +183,8 @@ __device__ void score_phase(const MetricSrc &src, int B, int Nv, int b, const qu
     }
     __syncthreads();            // every metric key has been read: slot 0 becomes the score keys
 #pragma unroll
-    for (int r = 0; r < MAXV / 256; ++r) {
-        const int i = threadIdx.x + 256 * r;
+    for (int r = 0; r < PER; ++r) {
+        const int i = tid + SCORE_THREADS * r;
         if (i < Nv) mk[i] = (sc[r] != sc[r]) ? 0u : float_key(sc[r]);
     }
 }
@@ -219,14 +240,14 @@ __device__ void topk_phase(const uint32_t *keys, int Nv, int K, int32_t *__restr
 
 // K < 0: score only.  When K >= 0 the indices of the min(K, Nv) best tokens of
 // sequence b go to keep_idx[b][0..min(K,Nv)).
-__global__ __launch_bounds__(256) void score_topk_kernel(MetricSrc src, long stride_sq, int B, int Nv,
+__global__ __launch_bounds__(SCORE_THREADS) void score_topk_kernel(MetricSrc src, long stride_sq, int B, int Nv,
                                                          quota_score_params p,
                                                          float *__restrict__ score,
                                                          float *__restrict__ normed, int K,
                                                          int32_t *__restrict__ keep_idx)
 {
     __shared__ uint32_t mk[4 * MAXV];
-    __shared__ int hist[4 * 256];
+    __shared__ int hist[8 * 256];
     __shared__ float lohi[8];
     const int b = blockIdx.x;
     src.osq = (size_t)b * stride_sq;
@@ -236,7 +257,7 @@ __global__ __launch_bounds__(256) void score_topk_kernel(MetricSrc src, long str
     const int k = K < Nv ? K : Nv;
     int32_t *out = keep_idx + (size_t)b * k;
     if (k == Nv) {
-        for (int i = threadIdx.x; i < Nv; i += 256) out[i] = i;
+        for (int i = threadIdx.x; i < Nv; i += SCORE_THREADS) out[i] = i;
         return;
     }
     __syncthreads();
@@ -283,7 +304,7 @@ int quota_internal_score(const float *sumsq, const float *ressq, long stride_sq,
     if (Nv == 0) return QUOTA_OK;
     ProfScope prof(QUOTA_K_SCORE_TOKENS, 0, 20.0 * B * Nv, st);
     MetricSrc src{sumsq, ressq, cm_inter, cm_intra, nullptr, 0, nullptr, nullptr, 0, 0};
-    score_topk_kernel<<<dim3(B), dim3(256), 0, st>>>(src, stride_sq, B, Nv, *p, score, normed, -1,
+    score_topk_kernel<<<dim3(B), dim3(SCORE_THREADS), 0, st>>>(src, stride_sq, B, Nv, *p, score, normed, -1,
                                                      nullptr);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
@@ -309,7 +330,7 @@ int quota_internal_score_topk(const float *sumsq, const float *ressq, long strid
     ProfScope prof(QUOTA_K_SCORE_TOKENS, 0,
                    (partial ? 8.0 * H + 8 : 20.0) * B * Nv + 4.0 * B * (K < Nv ? K : Nv), st);
     MetricSrc src{sumsq, ressq, cm_inter, cm_intra, partial, H, cm_out_inter, cm_out_intra, 0, 0};
-    score_topk_kernel<<<dim3(B), dim3(256), 0, st>>>(src, stride_sq, B, Nv, *p, score, nullptr, K,
+    score_topk_kernel<<<dim3(B), dim3(SCORE_THREADS), 0, st>>>(src, stride_sq, B, Nv, *p, score, nullptr, K,
                                                      keep_idx);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
