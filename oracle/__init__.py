@@ -205,3 +205,4 @@ def budget(r: float, V0: int) -> int:
 
 from .layer import (prefill_layer, decode_layer, decode_attention, dequant_kv, cache_from_prefill,  # noqa: E402,F401
                     LayerWeights)
+from . import recipe  # noqa: E402,F401

@@ -36,6 +36,8 @@ CLASSES = [
     ("score_topk_kernel", "score_tokens"),
     ("topk_kernel", "topk_prune"),
     ("compact_rows_kernel", "compact_rows"),
+    ("decode_attention_kernel", "attention_decode"),
+    ("kv_append_rows_kernel", "kv_append_rows"),
     ("quantize_weights_kernel", "quantize_weights"),
     ("pack_weights_kernel", "pack_weights"),
 ]
@@ -67,13 +69,14 @@ def stats(csv_path, bench_path=None):
         a[0] += int(r["Calls"])
         a[1] += float(r["TotalDurationNs"])
     total = sum(a[1] for a in agg.values())
-    print(f"{'kernel':28s} {'calls':>7s} {'avg us (trace)':>15s} {'share':>7s} {'avg us (events, bench.py)':>27s}")
+    print(f"{'kernel':28s} {'calls':>7s} {'avg us (trace)':>15s} {'share':>7s} {'events: avg us':>15s} {'net of pair':>12s}")
     for cls, (calls, ns) in sorted(agg.items(), key=lambda kv: -kv[1][1]):
-        ev = bench and bench["kernels"].get(cls, {}).get("avg_us")
+        k = (bench and bench["kernels"].get(cls)) or {}
+        ev, net = k.get("avg_us"), k.get("avg_us_net")
         print(f"{cls:28s} {calls:7d} {ns / calls / 1e3:15.2f} {100 * ns / total:6.1f}% "
-              f"{'' if ev is None else format(ev, '27.2f')}")
+              f"{'' if ev is None else format(ev, '15.2f')} {'' if net is None else format(net, '12.2f')}")
     if bench:
-        print(f"\nbench.py line of the same run: {bench['value']} {bench['unit']}, {bench['ms_per_step']} ms/step, "
+        print(f"\nbench.py line (plain run of the same command, no profiler attached): {bench['value']} {bench['unit']}, {bench['ms_per_step']} ms/step, "
               f"roofline {json.dumps(bench['roofline'])}")
 
 
@@ -113,7 +116,7 @@ def traffic(fetch_csv, write_csv, copy_mib, bench_path=None):
     if bench:
         for cls, rec in out["kernels"].items():
             k = bench["kernels"].get(cls)
-            if k and k.get("GBps") and k.get("avg_us"):
+            if k and k.get("GBps") and k.get("avg_us"):      # GBps is algorithmic bytes / raw event time
                 rec["algorithmic_bytes"] = round(k["GBps"] * 1e9 * k["avg_us"] * 1e-6)
     print(json.dumps(out, indent=1))
 

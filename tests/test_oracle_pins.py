@@ -507,3 +507,62 @@ def test_decode_reads_only_its_own_sequence_and_all_of_its_cache():
     c3 = {k: v[:, 1:] for k, v in cache.items()}
     c = oracle.decode_layer(W, xn, pn, c3, cos, sin)
     assert not np.array_equal(a["o"], c["o"])
+
+
+# ---- offline budget allocation (Eq. 1-5) -----------------------------------------------------
+
+def test_recipe_eq1_sensitivity_closed_forms():
+    rec = oracle.recipe
+    ref = np.array([2.0, 4.0, 8.0])
+    assert rec.sensitivity(np.zeros(3), ref, 1e-6) == 0.0                       # x^q == x
+    assert abs(rec.sensitivity(ref, ref, 0.0) - 1.0) < 1e-15                    # x^q == 0
+    assert rec.sensitivity([1.0, 9.0, 2.0], [10.0, 10.0, 10.0], 0.0) == 0.2     # median, not mean
+    assert rec.sensitivity([1.0, 3.0], [10.0, 10.0], 0.0) == pytest.approx(0.2)  # even count: mid-point
+    a, b = wl.rng(1, "sens").uniform(0.1, 1, 9), wl.rng(2, "sens").uniform(1, 2, 9)
+    assert rec.sensitivity(3 * a, 3 * b, 0.0) == pytest.approx(rec.sensitivity(a, b, 0.0), rel=1e-14)
+    assert rec.sensitivity(a, b, 0.5) < rec.sensitivity(a, b, 0.0)              # eta only damps
+
+
+def test_recipe_eq2_worked_example_and_library_percentile(golden_dir):
+    rec = oracle.recipe
+    rows = [l.split() for l in open(os.path.join(golden_dir, "recipe_eq2_worked.txt")) if l[0] != "#"]
+    S = np.array([float(r[0]) for r in rows])
+    want = np.array([float(r[1]) for r in rows])
+    assert np.allclose(rec.normalize_sensitivity(S), want, rtol=0, atol=1e-15)
+    x = wl.rng(3, "pct").uniform(0, 10, 11)
+    for p in (10.0, 90.0, 37.5):
+        assert rec.percentile_linear(x, p) == pytest.approx(np.percentile(x, p), rel=1e-14)
+    # invariant to positive affine maps of the raw sensitivities; flat input -> 0.5
+    assert np.allclose(rec.normalize_sensitivity(3 * x + 7), rec.normalize_sensitivity(x), atol=1e-13)
+    assert np.array_equal(rec.normalize_sensitivity(np.full(4, 2.5)), np.full(4, 0.5))
+    out = rec.normalize_sensitivity(x)
+    assert out.min() == 0.1 and out.max() == 0.9                                 # heavy tails are capped
+
+
+def test_recipe_eq3_shares():
+    rec = oracle.recipe
+    s = np.array([0.1, 0.5, 0.9, 0.3])
+    pi = rec.layer_shares(s, 0.7)
+    assert abs(pi.sum() - 1.0) < 1e-15 and np.all(pi > 0)
+    assert np.array_equal(np.argsort(-pi), np.argsort(s))                        # less sensitive, larger drop share
+    assert np.allclose(rec.layer_shares(np.full(5, 0.4), 0.3), 0.2)              # equal sensitivities: uniform
+    assert np.allclose(rec.layer_shares(s, 1e9), 0.25, atol=1e-9)                # tau -> inf: uniform
+    two = rec.layer_shares(np.array([0.2, 0.8]), 0.5)                            # m = 2 closed form: logistic
+    assert two[0] == pytest.approx(1.0 / (1.0 + math.exp(-(0.8 - 0.2) / 0.5)), rel=1e-14)
+    assert rec.layer_shares(s, 0.05).max() > 0.98                                # small tau: winner takes all
+
+
+def test_recipe_eq4_eq5_schedule_and_budgets(golden_dir):
+    rec = oracle.recipe
+    m, p_min = 6, 0.3
+    r = rec.keep_schedule(np.full(m, 1.0 / m), p_min)                            # uniform shares: a straight ramp
+    assert np.allclose(r, 1.0 - (1.0 - p_min) * np.arange(1, m + 1) / m, atol=1e-15)
+    pi = rec.layer_shares(rec.normalize_sensitivity(wl.rng(4, "S").uniform(0.01, 0.2, 9)), 1.0)
+    r = rec.keep_schedule(pi, p_min)
+    assert np.all(np.diff(r) <= 0) and r.min() >= p_min and r[0] < 1.0
+    assert r[-1] == pytest.approx(p_min, abs=1e-15)                              # the whole drop budget is spent
+    K = rec.budgets(r, 576)
+    assert np.all(np.diff(K) <= 0) and K[-1] == 173                              # Table 4: 173 of 576 at ratio 0.3
+    assert rec.budgets([1.0, 0.0, 0.25, 0.1], 580).tolist() == [580, 0, 145, 58]  # integers are not bumped
+    full = rec.make_recipe(np.array([1.0, 2.0, 3.0, 4.0, 5.0]), 1.0, 0.3, 576)
+    assert np.allclose(full["s_norm"], [0.1, 0.1875, 0.5, 0.8125, 0.9]) and full["K"][-1] == 173
