@@ -287,6 +287,28 @@ int quota_prefill_layer(const quota_layer *L, quota_state *st, int K_l,
                         const quota_score_params *p, quota_kv_cache *cache,
                         const quota_taps *taps_opt, void *ws, void *stream);
 
+/* ---- offline budget allocation (Eq. 1-5; host arithmetic, HOST pointers) -- */
+
+/* Eq. 1 for one layer: S = median over the n calibration samples of
+ * diff_norm[i] / (ref_norm[i] + eta), with diff_norm = ||x^q - x||_2 and
+ * ref_norm = ||x||_2 measured by the caller (even n: mean of the two middle
+ * values).  QUOTA_ERR_INVALID_ARG for n <= 0, negative inputs or eta, or a
+ * zero denominator. */
+int quota_sensitivity(const double *diff_norm, const double *ref_norm, int n,
+                      double eta, double *S_out);
+
+/* Eq. 2-5: from the raw sensitivities S[m] of the ordered candidate layers to
+ * the deployable recipe.  S~ = clip((S - P10)/(P90 - P10), 0.1, 0.9) with
+ * linearly interpolated percentiles over the m values (0.5 for all when
+ * P90 == P10); pi = softmax((1 - S~)/tau); d_i = (1 - p_min) pi_i;
+ * r_i = max(p_min, 1 - sum_{j<=i} d_j); K_i = ceil(r_i V0 - 1e-9).
+ * r_out[m], K_out[m] required; s_norm_opt[m], pi_opt[m] optional.  The K_i are
+ * what quota_prefill_layer takes as K_l for candidate layer i.
+ * Requires m > 0, tau > 0, 0 <= p_min <= 1, V0 >= 0, finite S. */
+int quota_make_recipe(const double *S, int m, double tau, double p_min, int V0,
+                      double *s_norm_opt, double *pi_opt, double *r_out,
+                      int32_t *K_out);
+
 /* ---- decode over the pruned 4-bit KV cache ------------------------------- */
 
 /* Single-query attention of one new token per sequence over `cache` (deployment

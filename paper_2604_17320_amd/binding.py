@@ -216,6 +216,26 @@ def quota_prefill_layer(L: Layer, st: State, K_l, p: ScoreParams, cache: KVCache
            "quota_prefill_layer")
 
 
+def quota_sensitivity(diff_norm, ref_norm, eta: float) -> float:
+    """Eq. 1 for one layer from per-sample norms (host sequences of floats)."""
+    n = len(diff_norm)
+    a, b = (C.c_double * n)(*diff_norm), (C.c_double * n)(*ref_norm)
+    out = C.c_double(0.0)
+    _check(lib().quota_sensitivity(a, b, n, C.c_double(eta), C.byref(out)), "quota_sensitivity")
+    return out.value
+
+
+def quota_make_recipe(S, tau: float, p_min: float, V0: int):
+    """Eq. 2-5 on the host: returns dict(s_norm, pi, r, K) as Python lists."""
+    m = len(S)
+    s = (C.c_double * m)(*S)
+    sn, pi, r = (C.c_double * m)(), (C.c_double * m)(), (C.c_double * m)()
+    K = (C.c_int32 * m)()
+    _check(lib().quota_make_recipe(s, m, C.c_double(tau), C.c_double(p_min), int(V0), sn, pi, r, K),
+           "quota_make_recipe")
+    return dict(s_norm=list(sn), pi=list(pi), r=list(r), K=list(K))
+
+
 def quota_attention_decode(q, cache: KVCache, o):
     _check(lib().quota_attention_decode(_ptr(q, torch.float16), C.byref(cache), _ptr(o, torch.float16), _stream()),
            "quota_attention_decode")

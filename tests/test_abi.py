@@ -68,3 +68,31 @@ def test_null_and_shape_checks_come_before_device_work(lib):
     assert lib.quota_prefill_workspace_bytes(None, 1, 16) == 0
     lib.quota_attention_workspace_bytes.restype = C.c_size_t
     assert lib.quota_attention_workspace_bytes(1, 640, 32, 128) > 0
+
+
+def test_recipe_matches_the_oracle():
+    """Host-only entry points (Eq. 1-5): the library's recipe against the oracle's, on the CPU."""
+    import numpy as np
+    import oracle
+    from paper_2604_17320_amd import binding, workloads as wl
+    for seed, m, tau, p_min, V0 in [(0, 5, 1.0, 0.3, 576), (1, 12, 0.5, 0.1, 2880), (2, 1, 2.0, 0.5, 64),
+                                    (3, 30, 0.2, 0.25, 576)]:
+        S = wl.rng(seed, "S", m).lognormal(-3.0, 1.0, m)
+        ref = oracle.recipe.make_recipe(S, tau, p_min, V0)
+        got = binding.quota_make_recipe(S.tolist(), tau, p_min, V0)
+        assert np.allclose(got["s_norm"], ref["s_norm"], rtol=0, atol=1e-14)
+        assert np.allclose(got["pi"], ref["pi"], rtol=1e-13, atol=0)
+        assert np.allclose(got["r"], ref["r"], rtol=0, atol=1e-14)
+        for k_got, k_ref, r in zip(got["K"], ref["K"], ref["r"]):
+            assert k_got == k_ref or abs(r * V0 - round(r * V0)) < 1e-6      # equal unless r V0 sits on an integer
+        assert all(a >= b for a, b in zip(got["K"], got["K"][1:])) and got["K"][-1] >= int(np.ceil(p_min * V0 - 1e-9))
+    flat = binding.quota_make_recipe([0.2, 0.2, 0.2], 1.0, 0.3, 576)
+    assert flat["s_norm"] == [0.5, 0.5, 0.5] and flat["K"][-1] == 173
+    a = wl.rng(5, "n").uniform(0.1, 1, 8).tolist()
+    b = wl.rng(6, "n").uniform(1, 2, 8).tolist()
+    assert binding.quota_sensitivity(a, b, 1e-6) == pytest.approx(oracle.recipe.sensitivity(a, b, 1e-6), rel=1e-15)
+    for bad in [dict(S=[0.1], tau=0.0, p_min=0.3, V0=10), dict(S=[float("nan")], tau=1.0, p_min=0.3, V0=10),
+                dict(S=[0.1], tau=1.0, p_min=1.5, V0=10)]:
+        with pytest.raises(binding.QuotaError) as e:
+            binding.quota_make_recipe(**bad)
+        assert e.value.code == binding.ERR_INVALID_ARG
