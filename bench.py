@@ -60,6 +60,78 @@ def measured_traffic(kernel):
                         source="profiles/hbm_traffic_c3_stack.txt")
 
 
+def serving_shape_kernels(shape, seed, reps=20):
+    """The same kernels at the batched-serving shape (batch 16 x 704 tokens of the 7B model), where a
+    call moves >= 90 MB and the bandwidth kernels are out of the launch-latency regime: each kernel is
+    launched `reps` times back to back between one event pair, and its algorithmic bytes (or ops) per
+    second are set against the HBM (or int8 MFMA) peak.  Supplementary to the headline figure."""
+    import torch
+    from paper_2604_17320_amd import binding as qb, workloads as wl
+    from paper_2604_17320_amd.model import KVCache4, PackedLinear
+    B, N, d, H, dh, F = 16, 704, shape.d, shape.H, shape.dh, shape.F
+    M = B * N
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed + 77)
+    rnd = lambda *shp: torch.randn(shp, generator=g, device="cuda", dtype=torch.float32).to(torch.float16)
+    x, qkv, gu = rnd(M, d), rnd(M, 3 * d), rnd(M, 2 * F)
+    gamma = torch.ones(d, dtype=torch.float32, device="cuda")
+    qa = torch.empty((M, max(d, F) // 2), dtype=torch.uint8, device="cuda")
+    sa, sq, rq = (torch.empty(M, dtype=torch.float32, device="cuda") for _ in range(3))
+    cos, sin = wl.rope_tables(dh, N)
+    cosT, sinT = torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda()
+    pos = torch.arange(N, dtype=torch.int32, device="cuda").repeat(B)
+    q_rot, khat, vhat = (torch.empty((M, d), dtype=torch.float16, device="cuda") for _ in range(3))
+    kc, vc = (torch.empty((M, d // 2), dtype=torch.uint8, device="cuda") for _ in range(2))
+    ks, vs = (torch.empty((M, d // 64), dtype=torch.float16, device="cuda") for _ in range(2))
+    n_keep = 173 + 128
+    keep = torch.arange(n_keep, dtype=torch.int32, device="cuda").mul(2).repeat(B).contiguous()
+    cache = KVCache4(B, n_keep + 66, H, dh)
+    w = torch.randn((3 * d, d), generator=g, device="cuda", dtype=torch.float32) * 0.02
+    lin = PackedLinear.from_fp32(w)
+    del w
+    y = torch.empty((M, 3 * d), dtype=torch.float16, device="cuda")
+    q1 = rnd(B, d)
+    o1 = torch.empty((B, d), dtype=torch.float16, device="cuda")
+
+    def append():
+        cache.reset()
+        qb.quota_kv_quant_append(khat, vhat, B, N, H, dh, keep, n_keep, cache.desc)
+
+    def decode_attn():
+        cache.desc.len = n_keep + 65           # pruned prefix + 65 decoded tokens
+        qb.quota_attention_decode(q1, cache.desc, o1)
+
+    Md = float(M) * d
+    cases = [
+        ("quantize_act", lambda: qb.quota_quantize_act(x, M, d, d, qa, sa, sq, rq), 2.5 * Md, 0),
+        ("rmsnorm_quantize_act", lambda: qb.quota_rmsnorm_quantize_act(x, M, d, d, gamma, 1e-5, qa, sa, sq, rq), 2.5 * Md, 0),
+        ("silu_mul_quantize_act", lambda: qb.quota_silu_mul_quantize_act(gu, M, F, qa, sa), 4.5 * M * F, 0),
+        ("rope_kv_quant", lambda: qb.quota_rope_kv_quant(qkv, M, H, dh, pos, cosT, sinT, N, q_rot, khat, vhat, kc, ks, vc, vs),
+         Md * (6 + 6 + 1 + 1.0 / 16), 0),
+        ("kv_quant_append", append, B * n_keep * d * (4 + 1 + 1.0 / 16), 0),
+        ("attention_decode", decode_attn, B * (n_keep + 65) * (d + d / 16.0), 0),
+        ("w4a4_gemm qkv", lambda: qb.quota_w4a4_gemm(qa, sa, M, lin.desc, y, 3 * d), 0, 2.0 * M * 3 * d * d),
+    ]
+    out = {}
+    for name, fn, nbytes, ops in cases:
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        rec = dict(avg_us=round(us, 2))
+        if nbytes:
+            rec.update(GBps=round(nbytes / us / 1e3, 1), frac_hbm_peak=round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4))
+        if ops:
+            rec.update(TOPs=round(ops / us / 1e6, 1), frac_int8_peak=round(ops / us / 1e6 / PEAK_INT8_TOPS, 4))
+        out[name] = rec
+    return dict(shape=f"batch {B} x {N} tokens, d={d}, F={F} ({M} rows)", reps=reps, kernels=out)
+
+
 def cpu_baseline(shape, stack, budgets, rope, sample_layers, seed):
     """The oracle, as it stands, on a bounded sample: a few layers of the stack, each fed a
     synthetic hidden state with the row count that layer sees in the real run."""
@@ -107,6 +179,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--profile-steps", type=int, default=3)
+    ap.add_argument("--no-serving-shape", action="store_true",
+                    help="skip the supplementary per-kernel rates at the batch-16 serving shape")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain elementwise copy of this many MiB (read + write), untimed: "
                          "the known-size kernel that HBM traffic counters are scaled by")
@@ -229,6 +303,8 @@ def main():
                              frac_int8_peak=round(gemm_ops / (gemm_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 4)
                              if gemm_ms else None, step_ms=round(gemm_ms / args.profile_steps, 4)),
                kernels=kern)
+    if not args.no_serving_shape:
+        out["serving_shape_kernels"] = serving_shape_kernels(shape, args.seed)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(shape, stack, budgets, rope, sample_layers, args.seed)
     print(json.dumps(out))

@@ -171,7 +171,7 @@ __global__ __launch_bounds__(256) void compact_rows_kernel(
         double z0 = 0.0, z1 = 0.0;
         block_max_sum2<4>(a, z0, z1, sm);
         float s;
-        quantize_cached_row<false>(v, n16, a, oq_out + drow * n16, s);
+        quantize_cached_row<false, ROW_THREADS, ROW_MAXCHUNK>(v, n16, threadIdx.x, a, oq_out + drow * n16, s);
         if (threadIdx.x == 0) os_out[drow] = s;
     }
     for (int i = threadIdx.x; i < n16; i += 256) {          // d/8 dwords of codes per row

@@ -1,9 +1,10 @@
 // Quantizers of the W4A4 execution form: weight group quantizer + repack,
 // per-token int4 activation quantizer (the Q of Eq. 6) and its fused variants
 // (RMSNorm in front of QKV / gate-up, SwiGLU product in front of down).
-// All are row kernels: one 256-thread workgroup per row, the row cached in
-// registers as 16-byte chunks, block reductions for absmax / sums of squares,
-// one packed dword (8 codes) stored per chunk.  HBM-bound by design.
+// All are row kernels: one wave per row (four rows per workgroup) up to 4096
+// columns, one workgroup per row beyond; the row is cached in registers as
+// 16-byte chunks, absmax / sums of squares are wave or block reductions, one
+// packed dword (8 codes) is stored per chunk.  HBM-bound by design.
 #include "common.h"
 #include "internal.h"
 #include "rowquant.h"
@@ -57,40 +58,65 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
 
 // ------------------------------------------------- activation quantizers
 
-template <bool WANT_METRICS>
+// A row is owned by GROUP threads, each caching up to 8 chunks.  GROUP = 64 (rows of up to 4096
+// columns): one WAVE per row, four rows per workgroup -- a lane issues all its 16-byte loads back
+// to back, the reductions are wave shuffles and there is no workgroup barrier.  GROUP = 256 (up to
+// 16384 columns): the whole workgroup owns the row and reduces through LDS.
+// Below this many rows the launch cannot fill the chip with one wave per row, and a row is
+// finished sooner by a whole workgroup.
+#define ROW_WAVE_MIN_ROWS 2048
+
+template <int GROUP>
+__device__ __forceinline__ void group_reduce(float &mx, double &s0, double &s1, double *sm)
+{
+    if (GROUP == 64) { mx = wave_max(mx); s0 = wave_sum(s0); s1 = wave_sum(s1); }
+    else block_max_sum2<4>(mx, s0, s1, sm);
+}
+#define ROW_PROLOGUE()                                                                         \
+    __shared__ double sm[12];                                                                  \
+    constexpr int NCH = ROW_MAXCHUNK;                                                          \
+    const int lane = threadIdx.x % GROUP;                                                      \
+    const int row = blockIdx.x * (ROW_THREADS / GROUP) + threadIdx.x / GROUP;                  \
+    if (row >= M) return;     /* GROUP = 64: the whole wave leaves; GROUP = 256: never taken */ \
+    (void)sm
+
+template <bool WANT_METRICS, int GROUP>
 __global__ __launch_bounds__(ROW_THREADS) void quantize_act_kernel(
-    const f16 *__restrict__ x, int d, long ldx, int rows_per_seq, long seq_stride,
+    const f16 *__restrict__ x, int M, int d, long ldx, int rows_per_seq, long seq_stride,
     uint32_t *__restrict__ q, float *__restrict__ scale, float *__restrict__ sumsq,
     float *__restrict__ ressq)
 {
-    __shared__ double sm[12];
-    int row = blockIdx.x, nchunk = d >> 3;
+    ROW_PROLOGUE();
+    const int nchunk = d >> 3;
     const uint4 *xr = reinterpret_cast<const uint4 *>(
         x + (size_t)(row / rows_per_seq) * seq_stride + (size_t)(row % rows_per_seq) * ldx);
-    Pack16 v[ROW_MAXCHUNK];
+    Pack16 v[NCH];
     float a = 0.0f;
-    double ss = 0.0, zero = 0.0;
+    double ss = 0.0;
 #pragma unroll
-    for (int r = 0; r < ROW_MAXCHUNK; ++r) {
-        int c = threadIdx.x + ROW_THREADS * r;
+    for (int r = 0; r < NCH; ++r) {
+        int c = lane + GROUP * r;
+        if (c < nchunk) v[r].u = xr[c];
+    }
+#pragma unroll
+    for (int r = 0; r < NCH; ++r) {
+        int c = lane + GROUP * r;
         if (c < nchunk) {
-            v[r].u = xr[c];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 float f = (float)v[r].h[e];
                 a = fmaxf(a, fabsf(f));
-                if (WANT_METRICS) ss += (double)f * (double)f;
+                if (WANT_METRICS) ss = __builtin_fma((double)f, (double)f, ss);     // product exact in fp64
             }
         }
     }
-    block_max_sum2<4>(a, ss, zero, sm);
+    double zero = 0.0;
+    group_reduce<GROUP>(a, ss, zero, sm);
     float s;
-    double rs = quantize_cached_row<WANT_METRICS>(v, nchunk, a, q ? q + (size_t)row * nchunk : nullptr, s);
-    if (WANT_METRICS) {
-        float dummy = 0.0f;
-        block_max_sum2<4>(dummy, rs, zero, sm);
-    }
-    if (threadIdx.x == 0) {
+    double rs = quantize_cached_row<WANT_METRICS, GROUP, NCH>(v, nchunk, lane, a,
+                                                              q ? q + (size_t)row * nchunk : nullptr, s);
+    if (WANT_METRICS) { float dummy = 0.0f; group_reduce<GROUP>(dummy, rs, zero, sm); }
+    if (lane == 0) {
         if (scale) scale[row] = s;
         if (WANT_METRICS) {
             if (sumsq) sumsq[row] = (float)ss;
@@ -99,40 +125,45 @@ __global__ __launch_bounds__(ROW_THREADS) void quantize_act_kernel(
     }
 }
 
-template <bool WANT_METRICS>
+template <bool WANT_METRICS, int GROUP>
 __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
-    const f16 *__restrict__ x, int d, long ldx, const float *__restrict__ gamma, float eps,
+    const f16 *__restrict__ x, int M, int d, long ldx, const float *__restrict__ gamma, float eps,
     uint32_t *__restrict__ q, float *__restrict__ scale, float *__restrict__ sumsq,
     float *__restrict__ ressq, f16 *__restrict__ h_out)
 {
-    __shared__ double sm[12];
-    int row = blockIdx.x, nchunk = d >> 3;
+    ROW_PROLOGUE();
+    const int nchunk = d >> 3;
     const uint4 *xr = reinterpret_cast<const uint4 *>(x + (size_t)row * ldx);
-    Pack16 v[ROW_MAXCHUNK];
+    Pack16 v[NCH];
     float a_raw = 0.0f;
-    double ss = 0.0, zero = 0.0;
+    double ss = 0.0;
 #pragma unroll
-    for (int r = 0; r < ROW_MAXCHUNK; ++r) {
-        int c = threadIdx.x + ROW_THREADS * r;
+    for (int r = 0; r < NCH; ++r) {
+        int c = lane + GROUP * r;
+        if (c < nchunk) v[r].u = xr[c];
+    }
+#pragma unroll
+    for (int r = 0; r < NCH; ++r) {
+        int c = lane + GROUP * r;
         if (c < nchunk) {
-            v[r].u = xr[c];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 float f = (float)v[r].h[e];
                 a_raw = fmaxf(a_raw, fabsf(f));
-                ss += (double)f * (double)f;
+                ss = __builtin_fma((double)f, (double)f, ss);     // product exact in fp64
             }
         }
     }
-    block_max_sum2<4>(a_raw, ss, zero, sm);
+    double zero = 0.0;
+    group_reduce<GROUP>(a_raw, ss, zero, sm);
     float rn = (float)(1.0 / sqrt(ss / (double)d + (double)eps));
     float s_raw = 1.0f, inv_raw = 0.0f;
     if (a_raw != 0.0f) { s_raw = a_raw / 7.0f; inv_raw = 7.0f / a_raw; }
     float a = 0.0f;
     double rs = 0.0;
 #pragma unroll
-    for (int r = 0; r < ROW_MAXCHUNK; ++r) {
-        int c = threadIdx.x + ROW_THREADS * r;
+    for (int r = 0; r < NCH; ++r) {
+        int c = lane + GROUP * r;
         if (c < nchunk) {
             const float4 *gp = reinterpret_cast<const float4 *>(gamma + 8 * c);
             float4 g0 = gp[0], g1 = gp[1];
@@ -144,7 +175,7 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
                     int code = code_from(rintf(f * inv_raw));
                     float deq = (float)code * s_raw;
                     float rr = deq - f;
-                    rs += (double)rr * (double)rr;
+                    rs = __builtin_fma((double)rr, (double)rr, rs);
                 }
                 float hn = f * rn;
                 hn = hn * gm[e];
@@ -155,10 +186,10 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
             if (h_out) reinterpret_cast<uint4 *>(h_out + (size_t)row * d)[c] = v[r].u;
         }
     }
-    block_max_sum2<4>(a, rs, zero, sm);
+    group_reduce<GROUP>(a, rs, zero, sm);
     float s;
-    quantize_cached_row<false>(v, nchunk, a, q + (size_t)row * nchunk, s);
-    if (threadIdx.x == 0) {
+    quantize_cached_row<false, GROUP, NCH>(v, nchunk, lane, a, q + (size_t)row * nchunk, s);
+    if (lane == 0) {
         scale[row] = s;
         if (WANT_METRICS) {
             if (sumsq) sumsq[row] = (float)ss;
@@ -167,20 +198,20 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
     }
 }
 
+template <int GROUP>
 __global__ __launch_bounds__(ROW_THREADS) void silu_mul_quantize_act_kernel(
-    const f16 *__restrict__ gu, int F, uint32_t *__restrict__ q, float *__restrict__ scale,
+    const f16 *__restrict__ gu, int M, int F, uint32_t *__restrict__ q, float *__restrict__ scale,
     f16 *__restrict__ z_out, const f16 *__restrict__ z_inject)
 {
-    __shared__ double sm[12];
-    int row = blockIdx.x, nchunk = F >> 3;
+    ROW_PROLOGUE();
+    const int nchunk = F >> 3;
     const uint4 *gr = reinterpret_cast<const uint4 *>(gu + (size_t)row * 2 * F);
     const uint4 *ur = reinterpret_cast<const uint4 *>(gu + (size_t)row * 2 * F + F);
-    Pack16 v[ROW_MAXCHUNK];
+    Pack16 v[NCH];
     float a = 0.0f;
-    double z0 = 0.0, z1 = 0.0;
 #pragma unroll
-    for (int r = 0; r < ROW_MAXCHUNK; ++r) {
-        int c = threadIdx.x + ROW_THREADS * r;
+    for (int r = 0; r < NCH; ++r) {
+        int c = lane + GROUP * r;
         if (c < nchunk) {
             if (z_inject) {
                 v[r].u = reinterpret_cast<const uint4 *>(z_inject + (size_t)row * F)[c];
@@ -191,7 +222,9 @@ __global__ __launch_bounds__(ROW_THREADS) void silu_mul_quantize_act_kernel(
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     float gt = (float)g.h[e], up = (float)u.h[e];
-                    float sg = gt / (1.0f + expf(-gt));
+                    // silu(g) = g / (1 + e^-g) with the hardware exp2 and reciprocal (a few fp32 ulp,
+                    // far inside the fp16 rounding that follows)
+                    float sg = gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt));
                     v[r].h[e] = to_f16(sg * up);
                 }
             }
@@ -200,10 +233,11 @@ __global__ __launch_bounds__(ROW_THREADS) void silu_mul_quantize_act_kernel(
             if (z_out) reinterpret_cast<uint4 *>(z_out + (size_t)row * F)[c] = v[r].u;
         }
     }
-    block_max_sum2<4>(a, z0, z1, sm);
+    double z0 = 0.0, z1 = 0.0;
+    group_reduce<GROUP>(a, z0, z1, sm);
     float s;
-    quantize_cached_row<false>(v, nchunk, a, q + (size_t)row * nchunk, s);
-    if (threadIdx.x == 0) scale[row] = s;
+    quantize_cached_row<false, GROUP, NCH>(v, nchunk, lane, a, q + (size_t)row * nchunk, s);
+    if (lane == 0) scale[row] = s;
 }
 
 // ------------------------------------------------------------ host side
@@ -255,7 +289,7 @@ static int check_rows(const void *x, int M, int d, int ld, const void *q, const 
 {
     if (!x || !q || !scale) return QUOTA_ERR_NULL;
     if (M < 0 || d <= 0) return QUOTA_ERR_INVALID_ARG;
-    if (d % 8 != 0 || d > 8 * ROW_THREADS * ROW_MAXCHUNK || ld < d || ld % 8 != 0) return QUOTA_ERR_SHAPE;
+    if (d % 8 != 0 || d > ROW_MAXCOLS || ld < d || ld % 8 != 0) return QUOTA_ERR_SHAPE;
     return QUOTA_OK;
 }
 
@@ -267,12 +301,14 @@ extern "C" int quota_quantize_act(const void *x_f16, int M, int d, int ldx, uint
     if (M == 0) return QUOTA_OK;
     hipStream_t st = (hipStream_t)stream;
     ProfScope prof(QUOTA_K_QUANTIZE_ACT, 0, 2.5 * M * d + 4.0 * M, st);
-    if (sumsq_opt || ressq_opt)
-        quantize_act_kernel<true><<<dim3(M), dim3(ROW_THREADS), 0, st>>>(
-            (const f16 *)x_f16, d, ldx, M, 0, (uint32_t *)q_packed, scale, sumsq_opt, ressq_opt);
-    else
-        quantize_act_kernel<false><<<dim3(M), dim3(ROW_THREADS), 0, st>>>(
-            (const f16 *)x_f16, d, ldx, M, 0, (uint32_t *)q_packed, scale, nullptr, nullptr);
+    const bool metrics = sumsq_opt || ressq_opt, small = d <= 4096 && M >= ROW_WAVE_MIN_ROWS;
+    const dim3 grid(small ? (M + 3) / 4 : M), blk(ROW_THREADS);
+    const f16 *x = (const f16 *)x_f16;
+    uint32_t *q = (uint32_t *)q_packed;
+    if (metrics && small) quantize_act_kernel<true, 64><<<grid, blk, 0, st>>>(x, M, d, ldx, M, 0, q, scale, sumsq_opt, ressq_opt);
+    else if (metrics) quantize_act_kernel<true, 256><<<grid, blk, 0, st>>>(x, M, d, ldx, M, 0, q, scale, sumsq_opt, ressq_opt);
+    else if (small) quantize_act_kernel<false, 64><<<grid, blk, 0, st>>>(x, M, d, ldx, M, 0, q, scale, nullptr, nullptr);
+    else quantize_act_kernel<false, 256><<<grid, blk, 0, st>>>(x, M, d, ldx, M, 0, q, scale, nullptr, nullptr);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
 }
@@ -289,14 +325,15 @@ extern "C" int quota_rmsnorm_quantize_act(const void *x_f16, int M, int d, int l
     if (M == 0) return QUOTA_OK;
     hipStream_t st = (hipStream_t)stream;
     ProfScope prof(QUOTA_K_RMSNORM_QUANTIZE_ACT, 0, 2.5 * M * d + 4.0 * M + 4.0 * d, st);
-    if (sumsq_opt || ressq_opt)
-        rmsnorm_quantize_act_kernel<true><<<dim3(M), dim3(ROW_THREADS), 0, st>>>(
-            (const f16 *)x_f16, d, ldx, gamma, eps, (uint32_t *)q_packed, scale, sumsq_opt,
-            ressq_opt, (f16 *)h_opt);
-    else
-        rmsnorm_quantize_act_kernel<false><<<dim3(M), dim3(ROW_THREADS), 0, st>>>(
-            (const f16 *)x_f16, d, ldx, gamma, eps, (uint32_t *)q_packed, scale, nullptr, nullptr,
-            (f16 *)h_opt);
+    const bool metrics = sumsq_opt || ressq_opt, small = d <= 4096 && M >= ROW_WAVE_MIN_ROWS;
+    const dim3 grid(small ? (M + 3) / 4 : M), blk(ROW_THREADS);
+    const f16 *x = (const f16 *)x_f16;
+    uint32_t *q = (uint32_t *)q_packed;
+    f16 *h = (f16 *)h_opt;
+    if (metrics && small) rmsnorm_quantize_act_kernel<true, 64><<<grid, blk, 0, st>>>(x, M, d, ldx, gamma, eps, q, scale, sumsq_opt, ressq_opt, h);
+    else if (metrics) rmsnorm_quantize_act_kernel<true, 256><<<grid, blk, 0, st>>>(x, M, d, ldx, gamma, eps, q, scale, sumsq_opt, ressq_opt, h);
+    else if (small) rmsnorm_quantize_act_kernel<false, 64><<<grid, blk, 0, st>>>(x, M, d, ldx, gamma, eps, q, scale, nullptr, nullptr, h);
+    else rmsnorm_quantize_act_kernel<false, 256><<<grid, blk, 0, st>>>(x, M, d, ldx, gamma, eps, q, scale, nullptr, nullptr, h);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
 }
@@ -309,8 +346,14 @@ extern "C" int quota_silu_mul_quantize_act(const void *gu_f16, int M, int F, uin
     if (rc != QUOTA_OK) return rc;
     if (M == 0) return QUOTA_OK;
     ProfScope prof(QUOTA_K_SILU_MUL_QUANTIZE_ACT, 0, 4.5 * M * F + 4.0 * M, (hipStream_t)stream);
-    silu_mul_quantize_act_kernel<<<dim3(M), dim3(ROW_THREADS), 0, (hipStream_t)stream>>>(
-        (const f16 *)gu_f16, F, (uint32_t *)q_packed, scale, (f16 *)z_opt, (const f16 *)z_inject_opt);
+    const bool small = F <= 4096 && M >= ROW_WAVE_MIN_ROWS;
+    const dim3 grid(small ? (M + 3) / 4 : M), blk(ROW_THREADS);
+    if (small)
+        silu_mul_quantize_act_kernel<64><<<grid, blk, 0, (hipStream_t)stream>>>(
+            (const f16 *)gu_f16, M, F, (uint32_t *)q_packed, scale, (f16 *)z_opt, (const f16 *)z_inject_opt);
+    else
+        silu_mul_quantize_act_kernel<256><<<grid, blk, 0, (hipStream_t)stream>>>(
+            (const f16 *)gu_f16, M, F, (uint32_t *)q_packed, scale, (f16 *)z_opt, (const f16 *)z_inject_opt);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
 }
@@ -322,12 +365,18 @@ int quota_internal_vector_metrics(const void *v_f16, int B, int Nv, int d, int l
 {
     if (!v_f16 || !sumsq || !ressq) return QUOTA_ERR_NULL;
     if (B <= 0 || Nv < 0 || d <= 0) return QUOTA_ERR_INVALID_ARG;
-    if (d % 8 != 0 || d > 8 * ROW_THREADS * ROW_MAXCHUNK || ldv < d || ldv % 8 != 0 || stride_b % 8 != 0)
+    if (d % 8 != 0 || d > ROW_MAXCOLS || ldv < d || ldv % 8 != 0 || stride_b % 8 != 0)
         return QUOTA_ERR_SHAPE;
     if (Nv == 0) return QUOTA_OK;
     ProfScope prof(QUOTA_K_QUANTIZE_ACT, 0, 2.0 * B * Nv * d + 8.0 * B * Nv, st);
-    quantize_act_kernel<true><<<dim3(B * Nv), dim3(ROW_THREADS), 0, st>>>(
-        (const f16 *)v_f16, d, ldv, Nv, stride_b, nullptr, nullptr, sumsq, ressq);
+    const bool small = d <= 4096 && B * Nv >= ROW_WAVE_MIN_ROWS;
+    const dim3 grid(small ? (B * Nv + 3) / 4 : B * Nv), blk(ROW_THREADS);
+    if (small)
+        quantize_act_kernel<true, 64><<<grid, blk, 0, st>>>((const f16 *)v_f16, B * Nv, d, ldv, Nv, stride_b,
+                                                           nullptr, nullptr, sumsq, ressq);
+    else
+        quantize_act_kernel<true, 256><<<grid, blk, 0, st>>>((const f16 *)v_f16, B * Nv, d, ldv, Nv, stride_b,
+                                                            nullptr, nullptr, sumsq, ressq);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
 }

@@ -1,15 +1,17 @@
-// Row-quantizer pieces shared by the row kernels (one 256-thread workgroup per row, the row
-// cached in registers as 16-byte chunks: chunk c of the row belongs to thread c % 256).
+// Row-quantizer pieces shared by the row kernels.  A row is owned by a GROUP of threads (one wave,
+// or a whole 256-thread workgroup) and cached in registers as 16-byte chunks: chunk c belongs to
+// thread c % GROUP of the group, as its (c / GROUP)-th chunk.
 #pragma once
 #include "common.h"
 
 #define ROW_THREADS 256
-#define ROW_MAXCHUNK 8   // 8 chunks * 8 halves * 256 threads = 16384 columns
+#define ROW_MAXCHUNK 8   // workgroup-per-row kernels: 8 chunks * 8 halves * 256 threads = 16384 columns
+#define ROW_MAXCOLS 16384
 
-// final phase shared by the three row kernels: quantize the cached row `v`
-// with absmax `a`, store packed codes, return this thread's residual sum.
-template <bool WANT_RES>
-__device__ __forceinline__ double quantize_cached_row(const Pack16 *v, int nchunk, float a,
+// final phase shared by the row kernels: quantize the cached row `v` with absmax `a`, store the
+// packed codes, return this thread's share of the residual sum of squares.
+template <bool WANT_RES, int GROUP, int NCH>
+__device__ __forceinline__ double quantize_cached_row(const Pack16 *v, int nchunk, int idx, float a,
                                                       uint32_t *__restrict__ qrow, float &s_out)
 {
     float s = 1.0f, inv = 0.0f;
@@ -17,8 +19,8 @@ __device__ __forceinline__ double quantize_cached_row(const Pack16 *v, int nchun
     s_out = s;
     double rs = 0.0;
 #pragma unroll
-    for (int r = 0; r < ROW_MAXCHUNK; ++r) {
-        int c = threadIdx.x + ROW_THREADS * r;
+    for (int r = 0; r < NCH; ++r) {
+        int c = idx + GROUP * r;
         if (c < nchunk) {
             uint32_t word = 0;
 #pragma unroll
@@ -29,7 +31,7 @@ __device__ __forceinline__ double quantize_cached_row(const Pack16 *v, int nchun
                 if (WANT_RES) {
                     float deq = (float)code * s;
                     float rr = deq - f;
-                    rs += (double)rr * (double)rr;
+                    rs = __builtin_fma((double)rr, (double)rr, rs);     // product exact in fp64
                 }
             }
             if (qrow) qrow[c] = word;
@@ -37,4 +39,3 @@ __device__ __forceinline__ double quantize_cached_row(const Pack16 *v, int nchun
     }
     return rs;
 }
-
