@@ -102,13 +102,23 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
 
     const int cl = tid % WPT, tl = tid / WPT;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int t = tl; t < L; t += TL) {
-        const size_t row = (size_t)b * capacity + t;
-        const uint32_t w = vc[row * n32 + h * WPT + cl];
-        const float s = (float)vs[row * ng + h * GPT + (cl >> 3)];
-        const float p = sc[t];
+    constexpr int UN = 8;                   // tokens in flight per thread: loads first, then the math
+    for (int t0 = tl; t0 < L; t0 += TL * UN) {
+        uint32_t w[UN];
+        float sv[UN], pv[UN];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = fmaf(p, (float)(f16)(code_at(w, e) * s), acc[e]);
+        for (int i = 0; i < UN; ++i) {
+            const int t = t0 + TL * i;
+            const bool ok = t < L;
+            const size_t row = (size_t)b * capacity + (ok ? t : 0);
+            w[i] = vc[row * n32 + h * WPT + cl];
+            sv[i] = (float)vs[row * ng + h * GPT + (cl >> 3)];
+            pv[i] = ok ? sc[t] : 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < UN; ++i)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(pv[i], (float)(f16)(code_at(w[i], e) * sv[i]), acc[e]);
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) red[tl * DH + 8 * cl + e] = acc[e];
