@@ -21,6 +21,8 @@
 // (high nibbles) int8 vectors; lane half h of k-step ks takes the even (ks
 // even) or odd (ks odd) vector of chunk 2*h + ks/2.
 #include "common.h"
+#include "internal.h"
+#include "ropequant.h"
 
 namespace {
 
@@ -50,12 +52,12 @@ __device__ __forceinline__ int xcd_remap(int pid, int total)
 // Workgroup tile (32*TM) x (128*TN); wave w owns columns [w*32*TN, (w+1)*32*TN).
 // CH > 0: the LDS stage holds CH groups of activations, so the workgroup meets at a
 // barrier once per CH groups instead of once per group (DEPTH must be a multiple of CH).
-template <int TM, int TN, int DEPTH, int CH, bool PIPE, bool ACC_OUT>
+template <int TM, int TN, int DEPTH, int CH, bool PIPE, bool ACC_OUT, bool QKV>
 __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
     const uint8_t *__restrict__ qa, const float *__restrict__ sa, int M, int K, int G,
     const uint4 *__restrict__ wp, const f16 *__restrict__ sw, int N, f16 *__restrict__ y, int ldy,
     const f16 *__restrict__ res, int ldr, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n,
-    int vec_store)
+    int vec_store, quota_qkv_epilogue qe)
 {
     constexpr int BM = 32 * TM, WN = 32 * TN, BN = 4 * WN;
     constexpr int LA = (BM * 4 + 255) / 256;         // 16-byte activation loads per thread per group
@@ -64,7 +66,8 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
     constexpr bool CHUNK = CH > 0;
     constexpr int CHN = CHUNK ? CH : 1;
     static_assert(DEPTH % CHN == 0, "DEPTH must be a multiple of CH");
-    constexpr int LDS_A = 2 * CHN * ASTAGE, LDS_C = 4 * 32 * CROW / 8;     // in uint4
+    constexpr int TROW = BN + 8;                     // halves per row of the workgroup-wide QKV tile
+    constexpr int LDS_A = 2 * CHN * ASTAGE, LDS_C = (QKV ? 32 * TROW : 4 * 32 * CROW) / 8;     // in uint4
     __shared__ uint4 lds_raw[LDS_A > LDS_C ? LDS_A : LDS_C];
 
     const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
@@ -299,6 +302,76 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
     // epilogue: token scale (with the 2^-8 of the shifted operands), residual, fp16.
     // With an aligned output the fp16 tile goes through LDS (the activation buffers
     // are free after the last barrier) so that every lane stores 16 contiguous bytes.
+    if constexpr (QKV) {
+        // Fused epilogue of the QKV projection: the fp16 tile (whole heads: the tile width
+        // divides the model width and is a multiple of the head size) is staged in LDS by all
+        // four waves; then every thread takes (row, 8-channel chunk) items and applies RoPE at
+        // the token's position id (q and k tiles) and the 4-bit K/V group quantizer (k and v
+        // tiles) exactly as the stand-alone kernel does.  q | k | v are column ranges
+        // [0,d) [d,2d) [2d,3d), so a tile lies in one of them.
+        f16 *tile = reinterpret_cast<f16 *>(lds_raw);
+        const int d = qe.d, region = n0 / d, c0 = n0 - region * d;     // tile-uniform
+        const int CPH = qe.dh >> 3, HALF = CPH >> 1, cpr = d >> 3, gpr = d >> 6;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            if (i) __syncthreads();                   // the previous row block has been read
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = 8 * (r >> 2) + 4 * hl + (r & 3);
+                const int m = m0 + 32 * i + row;
+                const float sam = sa[m < M ? m : M - 1] * 0.00390625f;
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    tile[row * TROW + wave * WN + 32 * j + l32] = to_f16(yacc[i][j][r] * sam);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < 32 * (BN / 8) / 256; ++q) {
+                const int idx = q * 256 + tid, row = idx / (BN / 8), c = idx % (BN / 8);
+                const int m = m0 + 32 * i + row;
+                const bool m_ok = m < M;
+                const int mm = m_ok ? m : M - 1;
+                Pack16 x, xp, out;
+                x.u = *reinterpret_cast<const uint4 *>(tile + row * TROW + 8 * c);
+                if (y && m_ok) *reinterpret_cast<uint4 *>(y + (size_t)m * ldy + n0 + 8 * c) = x.u;
+                const int col = c0 + 8 * c;           // first channel of the chunk inside q, k or v
+                if (region < 2) {
+                    const int cc = c % CPH;
+                    xp.u = *reinterpret_cast<const uint4 *>(tile + row * TROW + 8 * (c ^ HALF));
+                    const int pr = min(max(qe.pos[mm], 0), qe.n_pos - 1);
+                    const float *cp = qe.cosT + (size_t)pr * (qe.dh >> 1) + 8 * (cc % HALF);
+                    const float *sp = qe.sinT + (size_t)pr * (qe.dh >> 1) + 8 * (cc % HALF);
+                    float cs[8], sn[8];
+                    *reinterpret_cast<float4 *>(cs) = *reinterpret_cast<const float4 *>(cp);
+                    *reinterpret_cast<float4 *>(cs + 4) = *reinterpret_cast<const float4 *>(cp + 4);
+                    *reinterpret_cast<float4 *>(sn) = *reinterpret_cast<const float4 *>(sp);
+                    *reinterpret_cast<float4 *>(sn + 4) = *reinterpret_cast<const float4 *>(sp + 4);
+                    rope8(x, xp, cs, sn, cc >= HALF, out);
+                } else {
+                    out = x;
+                }
+                if (region == 0) {
+                    if (m_ok) *reinterpret_cast<uint4 *>(qe.q_rot + (size_t)m * d + col) = out.u;
+                } else {
+                    float f[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) f[e] = (float)out.h[e];
+                    Pack16 hat;
+                    f16 sc;
+                    const uint32_t word = kv_quant8(f, &sc, &hat);     // all 8 lanes of a group take part
+                    if (m_ok) {
+                        f16 *xh = region == 1 ? qe.khat : qe.vhat;
+                        uint32_t *codes = region == 1 ? qe.k_codes : qe.v_codes;
+                        f16 *scales = region == 1 ? qe.k_scales : qe.v_scales;
+                        *reinterpret_cast<uint4 *>(xh + (size_t)m * d + col) = hat.u;
+                        codes[(size_t)m * cpr + (col >> 3)] = word;
+                        if ((c & 7) == 0) scales[(size_t)m * gpr + (col >> 6)] = sc;
+                    }
+                }
+            }
+        }
+        return;
+    }
     f16 *cw = reinterpret_cast<f16 *>(lds_raw) + wave * 32 * CROW;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -334,24 +407,58 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
     }
 }
 
-template <int TM, int TN, int DEPTH, int CH, bool PIPE, bool ACC_OUT>
+template <int TM, int TN, int DEPTH, int CH, bool PIPE, bool ACC_OUT, bool QKV = false>
 int launch(int kernel_id, const uint8_t *qa, const float *sa, int M, const quota_weights *W, f16 *y,
-           int ldy, const f16 *res, int ldr, int32_t *acc, hipStream_t st)
+           int ldy, const f16 *res, int ldr, int32_t *acc, hipStream_t st,
+           const quota_qkv_epilogue *qe = nullptr)
 {
     constexpr int BM = 32 * TM, BN = 128 * TN;
     int G = (W->K + QUOTA_GROUP_W - 1) / QUOTA_GROUP_W;
     int tiles_m = (M + BM - 1) / BM, tiles_n = (W->N + BN - 1) / BN;
     const double Md = M, Nd = W->N, Kd = W->K;
     ProfScope prof(kernel_id, 2.0 * Md * Nd * Kd,
-                   Nd * Kd / 2 + 2.0 * Nd * G + Md * Kd / 2 + 4 * Md + 2.0 * Md * Nd * (res ? 2 : 1), st);
-    w4a4_gemm_kernel<TM, TN, DEPTH, CH, PIPE, ACC_OUT><<<dim3(tiles_m * tiles_n), dim3(256), 0, st>>>(
+                   Nd * Kd / 2 + 2.0 * Nd * G + Md * Kd / 2 + 4 * Md +
+                       (QKV ? Md * (Nd / 3) * (7 + 1.0 / 16) + 4 * Md : 2.0 * Md * Nd * (res ? 2 : 1)), st);
+    static const quota_qkv_epilogue no_qe = {};
+    w4a4_gemm_kernel<TM, TN, DEPTH, CH, PIPE, ACC_OUT, QKV><<<dim3(tiles_m * tiles_n), dim3(256), 0, st>>>(
         qa, sa, M, W->K, G, (const uint4 *)W->packed, (const f16 *)W->scales, W->N, y, ldy, res, ldr,
-        acc, tiles_m, tiles_n, (y && ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0) ? 1 : 0);
+        acc, tiles_m, tiles_n, (y && ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0) ? 1 : 0,
+        qe ? *qe : no_qe);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
 }
 
 }  // namespace
+
+// Tile choice by a small cost model fitted to measured kernel times on this GPU (us).
+// W workgroups run R at a time per CU on 256 CUs; a launch that fits (W <= 256 R) costs
+// c0 + G * u[workgroups per CU - 1], a larger one c0 + G * u[R-1] * (f0 + f1 * W / (256 R)).
+// Wide tiles reuse each unpacked weight for 64 rows but need full rounds; the 32-row tiles
+// spread small problems over more waves; the deep variant prefetches weights 8 groups
+// ahead for launches of at most one workgroup per CU.  `allow_wide` = false leaves the
+// 256-column tile out.
+static int choose_tile(int M, int N, int K, bool allow_wide)
+{
+    struct Tile { int bm, bn, R; float c0, u[3], f0, f1; };
+    static const Tile tiles[4] = {
+        {64, 256, 2, 13.0f, {0.69f, 1.34f, 0.0f}, 0.0f, 1.22f},     // <2,2,3,0>
+        {64, 128, 2, 6.0f, {0.39f, 0.69f, 0.0f}, 0.0f, 1.27f},      // <2,1,4,2> pipelined
+        {32, 128, 3, 0.5f, {0.39f, 0.61f, 0.82f}, 0.35f, 0.92f},    // <1,1,4,2> pipelined
+        {32, 128, 2, 4.0f, {0.27f, 0.46f, 0.0f}, 0.0f, 1.45f},      // <1,1,8,4> pipelined, deep prefetch
+    };
+    const int G = (K + QUOTA_GROUP_W - 1) / QUOTA_GROUP_W;
+    int best = -1;
+    float best_t = 0.0f;
+    for (int i = allow_wide ? 0 : 1; i < 4; ++i) {
+        const Tile &t = tiles[i];
+        const long wgs = (long)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
+        const float x = (float)wgs / (256.0f * t.R);
+        const float est = x <= 1.0f ? t.c0 + G * t.u[(wgs + 255) / 256 - 1]
+                                    : t.c0 + G * t.u[t.R - 1] * (t.f0 + t.f1 * x);
+        if (best < 0 || est < best_t) { best = i; best_t = est; }
+    }
+    return best;
+}
 
 extern "C" int quota_w4a4_gemm(const uint8_t *qa, const float *sa, int M, const quota_weights *W,
                                void *y_f16, int ldy, const void *residual_opt, int ldr,
@@ -369,34 +476,34 @@ extern "C" int quota_w4a4_gemm(const uint8_t *qa, const float *sa, int M, const 
     const f16 *res = (const f16 *)residual_opt;
     if (acc_i32_opt)
         return launch<2, 1, 2, 0, false, true>(QUOTA_K_GEMM_OTHER, qa, sa, M, W, y, ldy, res, ldr, acc_i32_opt, st);
-    // Tile choice by a small cost model fitted to measured kernel times on this GPU (us).
-    // W workgroups run R at a time per CU on 256 CUs; a launch that fits (W <= 256 R) costs
-    // c0 + G * u[workgroups per CU - 1], a larger one c0 + G * u[R-1] * (f0 + f1 * W / (256 R)).
-    // Wide tiles reuse each unpacked weight for 64 rows but need full rounds; the 32-row tiles
-    // spread small problems over more waves; the deep variant prefetches weights 8 groups
-    // ahead for launches of at most one workgroup per CU.
-    struct Tile { int bm, bn, R; float c0, u[3], f0, f1; };
-    static const Tile tiles[4] = {
-        {64, 256, 2, 13.0f, {0.69f, 1.34f, 0.0f}, 0.0f, 1.22f},     // <2,2,3,0>
-        {64, 128, 2, 6.0f, {0.39f, 0.69f, 0.0f}, 0.0f, 1.27f},      // <2,1,4,2> pipelined
-        {32, 128, 3, 0.5f, {0.39f, 0.61f, 0.82f}, 0.35f, 0.92f},    // <1,1,4,2> pipelined
-        {32, 128, 2, 4.0f, {0.27f, 0.46f, 0.0f}, 0.0f, 1.45f},      // <1,1,8,4> pipelined, deep prefetch
-    };
-    const int G = (W->K + QUOTA_GROUP_W - 1) / QUOTA_GROUP_W;
-    int best = 0;
-    float best_t = 0.0f;
-    for (int i = 0; i < 4; ++i) {
-        const Tile &t = tiles[i];
-        const long wgs = (long)((M + t.bm - 1) / t.bm) * ((W->N + t.bn - 1) / t.bn);
-        const float x = (float)wgs / (256.0f * t.R);
-        const float est = x <= 1.0f ? t.c0 + G * t.u[(wgs + 255) / 256 - 1]
-                                    : t.c0 + G * t.u[t.R - 1] * (t.f0 + t.f1 * x);
-        if (i == 0 || est < best_t) { best = i; best_t = est; }
-    }
-    switch (best) {
+    switch (choose_tile(M, W->N, W->K, true)) {
     case 0: return launch<2, 2, 3, 0, false, false>(QUOTA_K_GEMM_64X256, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
     case 1: return launch<2, 1, 4, 2, true, false>(QUOTA_K_GEMM_64X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
     case 2: return launch<1, 1, 4, 2, true, false>(QUOTA_K_GEMM_32X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
     default: return launch<1, 1, 8, 4, true, false>(QUOTA_K_GEMM_32X128_DEEP, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    }
+}
+
+// QKV projection with the RoPE + 4-bit K/V quantizer fused into the epilogue (see the kernel).
+// y_opt, when not null, also receives the plain fp16 q | k | v.  Returns QUOTA_ERR_SHAPE when the
+// shape does not fit the fused form (the caller then runs the two kernels separately).
+int quota_internal_w4a4_gemm_qkv(const uint8_t *qa, const float *sa, int M, const quota_weights *W,
+                                 void *y_opt, const quota_qkv_epilogue *qe, hipStream_t st)
+{
+    if (!qa || !sa || !W || !W->packed || !W->scales || !qe || !qe->pos || !qe->cosT || !qe->sinT ||
+        !qe->q_rot || !qe->khat || !qe->vhat || !qe->k_codes || !qe->k_scales || !qe->v_codes || !qe->v_scales)
+        return QUOTA_ERR_NULL;
+    if (M < 0 || qe->n_pos <= 0) return QUOTA_ERR_INVALID_ARG;
+    const int d = qe->d;
+    if ((qe->dh != 64 && qe->dh != 128) || d <= 0 || d % 128 != 0 || W->N != 3 * d || W->K % 32 != 0)
+        return QUOTA_ERR_SHAPE;
+    if (M == 0) return QUOTA_OK;
+    f16 *y = (f16 *)y_opt;
+    // (the 256-column tile is left out: with this epilogue it runs at its register limit)
+    switch (choose_tile(M, W->N, W->K, false)) {
+    case 0: return launch<2, 2, 3, 0, false, false, true>(QUOTA_K_GEMM_64X256, qa, sa, M, W, y, 3 * d, nullptr, 0, nullptr, st, qe);
+    case 1: return launch<2, 1, 4, 2, true, false, true>(QUOTA_K_GEMM_64X128, qa, sa, M, W, y, 3 * d, nullptr, 0, nullptr, st, qe);
+    case 2: return launch<1, 1, 4, 2, true, false, true>(QUOTA_K_GEMM_32X128, qa, sa, M, W, y, 3 * d, nullptr, 0, nullptr, st, qe);
+    default: return launch<1, 1, 8, 4, true, false, true>(QUOTA_K_GEMM_32X128_DEEP, qa, sa, M, W, y, 3 * d, nullptr, 0, nullptr, st, qe);
     }
 }

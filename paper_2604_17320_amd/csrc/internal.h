@@ -44,3 +44,15 @@ int quota_internal_vector_metrics(const void *v_f16, int B, int Nv, int d, int l
 // sequence and advances cache->len by 1.  QUOTA_ERR_CAPACITY if the cache is full.
 int quota_internal_kv_append_rows(int d, const uint8_t *skc, const void *sks, const uint8_t *svc,
                                   const void *svs, quota_kv_cache *cache, hipStream_t st);
+
+// Arguments of the fused QKV epilogue: what quota_rope_kv_quant takes, minus the qkv input.
+struct quota_qkv_epilogue {
+    const int32_t *pos;
+    const float *cosT, *sinT;
+    int n_pos, d, dh;
+    f16 *q_rot, *khat, *vhat;
+    uint32_t *k_codes, *v_codes;
+    f16 *k_scales, *v_scales;
+};
+int quota_internal_w4a4_gemm_qkv(const uint8_t *qa, const float *sa, int M, const quota_weights *W,
+                                 void *y_opt, const quota_qkv_epilogue *qe, hipStream_t st);

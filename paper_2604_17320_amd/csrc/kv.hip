@@ -5,33 +5,9 @@
 #include "common.h"
 #include "internal.h"
 #include "rowquant.h"
+#include "ropequant.h"
 
 namespace {
-
-// Quantize this lane's 8 channels; the 8 lanes [lane & ~7, +8) form one group.
-// Returns packed codes; *sh = fp16 group scale; xhat (optional) = code * scale.
-__device__ __forceinline__ uint32_t kv_quant8(const float f[8], f16 *sh_out, Pack16 *xhat)
-{
-    float a = 0.0f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(f[e]));
-    a = fmaxf(a, __shfl_xor(a, 1, 64));
-    a = fmaxf(a, __shfl_xor(a, 2, 64));
-    a = fmaxf(a, __shfl_xor(a, 4, 64));
-    f16 sh = to_f16(a / 7.0f);
-    float s = (float)sh;
-    if (a == 0.0f || s == 0.0f) { sh = (f16)1.0f; s = 1.0f; }
-    float r = 1.0f / s;
-    uint32_t word = 0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        int code = code_from(rintf(f[e] * r));
-        word |= (uint32_t)(code & 0xF) << (4 * e);
-        if (xhat) xhat->h[e] = to_f16((float)code * s);
-    }
-    *sh_out = sh;
-    return word;
-}
 
 // thread t -> (row, 8-channel chunk c); q | k | v chunks at the same c
 template <int DH>
@@ -67,16 +43,13 @@ __global__ __launch_bounds__(256) void rope_kv_quant_kernel(
     *reinterpret_cast<float4 *>(cs + 4) = *reinterpret_cast<const float4 *>(cp + 4);
     *reinterpret_cast<float4 *>(sn) = *reinterpret_cast<const float4 *>(sp);
     *reinterpret_cast<float4 *>(sn + 4) = *reinterpret_cast<const float4 *>(sp + 4);
-    Pack16 qo;
+    Pack16 qo, ko;
     float kf[8], vf[8];
+    rope8(q, qp, cs, sn, second, qo);
+    rope8(k, kp, cs, sn, second, ko);            // rotated k is an fp16 tensor
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        float a = (float)q.h[e] * cs[e];
-        float b = (float)qp.h[e] * sn[e];
-        qo.h[e] = to_f16(second ? a + b : a - b);
-        float a2 = (float)k.h[e] * cs[e];
-        float b2 = (float)kp.h[e] * sn[e];
-        kf[e] = (float)to_f16(second ? a2 + b2 : a2 - b2);   // rotated k is an fp16 tensor
+        kf[e] = (float)ko.h[e];
         vf[e] = (float)v.h[e];
     }
     *reinterpret_cast<uint4 *>(q_rot + (size_t)row * d + 8 * c) = qo.u;

@@ -90,6 +90,26 @@ int dump(void *dst, const void *src, size_t bytes, hipStream_t st)
         if (rc_ != QUOTA_OK) return rc_;  \
     } while (0)
 
+// QKV projection of the quantized rows in w.qa, RoPE at `pos`, 4-bit K/V of every row: one
+// kernel (the GEMM with the fused epilogue) when the shape allows it, else the GEMM followed by
+// the stand-alone RoPE/KV kernel.  Both give the same bits.  want_qkv: also keep the plain
+// projection output in w.qkv.
+static int qkv_rope_kv_quant(const quota_layer *L, const LayerWs &w, int M, const int32_t *pos,
+                             bool want_qkv, hipStream_t st)
+{
+    const int d = L->H * L->dh;
+    quota_qkv_epilogue qe;
+    qe.pos = pos; qe.cosT = L->cosT; qe.sinT = L->sinT; qe.n_pos = L->n_pos; qe.d = d; qe.dh = L->dh;
+    qe.q_rot = w.q_rot; qe.khat = w.khat; qe.vhat = w.vhat;
+    qe.k_codes = (uint32_t *)w.skc; qe.v_codes = (uint32_t *)w.svc;
+    qe.k_scales = w.sks; qe.v_scales = w.svs;
+    int rc = quota_internal_w4a4_gemm_qkv(w.qa, w.sa, M, &L->qkv, want_qkv ? w.qkv : nullptr, &qe, st);
+    if (rc != QUOTA_ERR_SHAPE) return rc;
+    TRY(quota_w4a4_gemm(w.qa, w.sa, M, &L->qkv, w.qkv, 3 * d, nullptr, 0, nullptr, st));
+    return quota_rope_kv_quant(w.qkv, M, L->H, L->dh, pos, L->cosT, L->sinT, L->n_pos, w.q_rot, w.khat,
+                               w.vhat, w.skc, w.sks, w.svc, w.svs, st);
+}
+
 extern "C" size_t quota_prefill_workspace_bytes(const quota_layer *L, int B, int N)
 {
     if (!L || B <= 0 || N <= 0 || L->H <= 0 || L->dh <= 0 || L->F <= 0) return 0;
@@ -124,10 +144,8 @@ extern "C" int quota_prefill_layer(const quota_layer *L, quota_state *s, int K_l
     // attention half on every token that entered the layer
     TRY(quota_rmsnorm_quantize_act(s->x, M, d, d, L->gamma1, L->eps, w.qa, w.sa, w.sumsq, w.ressq,
                                    nullptr, st));
-    TRY(quota_w4a4_gemm(w.qa, w.sa, M, &L->qkv, w.qkv, 3 * d, nullptr, 0, nullptr, st));
+    TRY(qkv_rope_kv_quant(L, w, M, s->pos, t->qkv != nullptr, st));
     TRY(dump(t->qkv, w.qkv, (size_t)M * 3 * d * 2, st));
-    TRY(quota_rope_kv_quant(w.qkv, M, H, dh, s->pos, L->cosT, L->sinT, L->n_pos, w.q_rot, w.khat,
-                            w.vhat, w.skc, w.sks, w.svc, w.svs, st));
     TRY(dump(t->q_rot, w.q_rot, (size_t)M * d * 2, st));
     const float *partial = nullptr;     // per-head column masses; their head mean is taken by the score kernel
     TRY(quota_internal_attention(w.q_rot, w.khat, w.vhat, B, N, H, dh, vb, Nv, w.o, true, w.attn_ws,
@@ -222,10 +240,8 @@ extern "C" int quota_decode_layer(const quota_layer *L, const void *x_f16, const
 
     TRY(quota_rmsnorm_quantize_act(x_f16, B, d, d, L->gamma1, L->eps, w.qa, w.sa, nullptr, nullptr,
                                    nullptr, st));
-    TRY(quota_w4a4_gemm(w.qa, w.sa, B, &L->qkv, w.qkv, 3 * d, nullptr, 0, nullptr, st));
+    TRY(qkv_rope_kv_quant(L, w, B, pos, t->qkv != nullptr, st));
     TRY(dump(t->qkv, w.qkv, (size_t)B * 3 * d * 2, st));
-    TRY(quota_rope_kv_quant(w.qkv, B, H, dh, pos, L->cosT, L->sinT, L->n_pos, w.q_rot, w.khat, w.vhat,
-                            w.skc, w.sks, w.svc, w.svs, st));
     TRY(dump(t->q_rot, w.q_rot, (size_t)B * d * 2, st));
     // the new token's K/V join the cache first; attention then reads all of it in 4-bit form
     TRY(quota_internal_kv_append_rows(d, w.skc, w.sks, w.svc, w.svs, cache, st));

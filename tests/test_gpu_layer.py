@@ -216,3 +216,26 @@ def test_layer_errors(qb):
     with pytest.raises(qb.QuotaError) as e:
         qb.quota_prefill_layer(L.desc, st_bad, 19, p, ok.desc, None, ws)
     assert e.value.code == qb.ERR_INVALID_ARG
+
+
+def test_layer_without_taps_equals_layer_with_taps(qb):
+    """The benchmark runs the layer with no dump taps (the QKV projection then keeps no plain copy of
+    its output); the result must be the same bits as the tapped run the parity tests check."""
+    from paper_2604_17320_amd.model import KVCache4
+    shape = wl.CONFIGS[0]
+    W, L, cos, sin = build_layer(shape, 2)
+    x, pos = wl.hidden_state(shape, 2), wl.positions(shape)
+    K = 19
+    tapped = run_gpu(qb, L, shape, x, pos, K)
+    n_keep = shape.N - shape.Nv + K
+    cache = KVCache4(1, n_keep, shape.H, shape.dh)
+    x_out = torch.zeros((n_keep, shape.d), dtype=torch.float16, device="cuda")
+    pos_out = torch.zeros((n_keep,), dtype=torch.int32, device="cuda")
+    ws = torch.empty(L.workspace_bytes(1, shape.N), dtype=torch.uint8, device="cuda")
+    xd, pd = dev(x), dev(pos)
+    st = qb.State(1, shape.N, 0, shape.Nv, xd.data_ptr(), pd.data_ptr(), x_out.data_ptr(), pos_out.data_ptr())
+    qb.quota_prefill_layer(L.desc, st, K, qb.quota_score_params_default(), cache.desc, None, ws)
+    assert np.array_equal(host(x_out).view(np.uint16), tapped["x_next"][:n_keep].view(np.uint16))
+    assert np.array_equal(host(pos_out), tapped["pos_next"][:n_keep])
+    assert np.array_equal(unpack4(host(cache.k_codes)[0, :n_keep]), tapped["cache_kc"])
+    assert np.array_equal(host(cache.v_scales)[0, :n_keep].view(np.uint16), tapped["cache_vs"].view(np.uint16))
