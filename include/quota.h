@@ -343,7 +343,7 @@ int quota_decode_layer(const quota_layer *L, const void *x_f16,
  * because each shape is a separate kernel (and a separate profiler row). */
 enum {
     QUOTA_K_QUANTIZE_ACT = 0, QUOTA_K_RMSNORM_QUANTIZE_ACT, QUOTA_K_SILU_MUL_QUANTIZE_ACT,
-    QUOTA_K_GEMM_64X256, QUOTA_K_GEMM_64X128, QUOTA_K_GEMM_32X128, QUOTA_K_GEMM_32X128_DEEP,
+    QUOTA_K_GEMM_64X256, QUOTA_K_GEMM_64X128, QUOTA_K_GEMM_32X128, QUOTA_K_GEMM_32X128_DEEP, QUOTA_K_GEMM_64X128_LEAN,
     QUOTA_K_GEMM_OTHER, QUOTA_K_ROPE_KV_QUANT,
     QUOTA_K_KV_QUANT_APPEND, QUOTA_K_ATTENTION_FWD, QUOTA_K_ATTENTION_COLMASS,
     QUOTA_K_SCORE_TOKENS, QUOTA_K_TOPK_PRUNE, QUOTA_K_COMPACT_ROWS, QUOTA_K_QUANTIZE_WEIGHTS,

@@ -52,8 +52,8 @@ __device__ __forceinline__ int xcd_remap(int pid, int total)
 // Workgroup tile (32*TM) x (128*TN); wave w owns columns [w*32*TN, (w+1)*32*TN).
 // CH > 0: the LDS stage holds CH groups of activations, so the workgroup meets at a
 // barrier once per CH groups instead of once per group (DEPTH must be a multiple of CH).
-template <int TM, int TN, int DEPTH, int CH, bool PIPE, bool ACC_OUT, bool QKV>
-__global__ __launch_bounds__(256) void w4a4_gemm_kernel(
+template <int TM, int TN, int DEPTH, int CH, bool PIPE, bool ACC_OUT, bool QKV, int WPE>
+__global__ __launch_bounds__(256, WPE) void w4a4_gemm_kernel(
     const uint8_t *__restrict__ qa, const float *__restrict__ sa, int M, int K, int G,
     const uint4 *__restrict__ wp, const f16 *__restrict__ sw, int N, f16 *__restrict__ y, int ldy,
     const f16 *__restrict__ res, int ldr, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n,
@@ -407,7 +407,7 @@ __global__ __launch_bounds__(256) void w4a4_gemm_kernel(
     }
 }
 
-template <int TM, int TN, int DEPTH, int CH, bool PIPE, bool ACC_OUT, bool QKV = false>
+template <int TM, int TN, int DEPTH, int CH, bool PIPE, bool ACC_OUT, bool QKV = false, int WPE = 1>
 int launch(int kernel_id, const uint8_t *qa, const float *sa, int M, const quota_weights *W, f16 *y,
            int ldy, const f16 *res, int ldr, int32_t *acc, hipStream_t st,
            const quota_qkv_epilogue *qe = nullptr)
@@ -420,7 +420,7 @@ int launch(int kernel_id, const uint8_t *qa, const float *sa, int M, const quota
                    Nd * Kd / 2 + 2.0 * Nd * G + Md * Kd / 2 + 4 * Md +
                        (QKV ? Md * (Nd / 3) * (7 + 1.0 / 16) + 4 * Md : 2.0 * Md * Nd * (res ? 2 : 1)), st);
     static const quota_qkv_epilogue no_qe = {};
-    w4a4_gemm_kernel<TM, TN, DEPTH, CH, PIPE, ACC_OUT, QKV><<<dim3(tiles_m * tiles_n), dim3(256), 0, st>>>(
+    w4a4_gemm_kernel<TM, TN, DEPTH, CH, PIPE, ACC_OUT, QKV, WPE><<<dim3(tiles_m * tiles_n), dim3(256), 0, st>>>(
         qa, sa, M, W->K, G, (const uint4 *)W->packed, (const f16 *)W->scales, W->N, y, ldy, res, ldr,
         acc, tiles_m, tiles_n, (y && ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0) ? 1 : 0,
         qe ? *qe : no_qe);
@@ -435,26 +435,31 @@ int launch(int kernel_id, const uint8_t *qa, const float *sa, int M, const quota
 // c0 + G * u[workgroups per CU - 1], a larger one c0 + G * u[R-1] * (f0 + f1 * W / (256 R)).
 // Wide tiles reuse each unpacked weight for 64 rows but need full rounds; the 32-row tiles
 // spread small problems over more waves; the deep variant prefetches weights 8 groups
-// ahead for launches of at most one workgroup per CU.  `allow_wide` = false leaves the
+// ahead for launches of at most one workgroup per CU; the lean 64x128 variant (no group
+// pipeline, registers capped so that three workgroups fit on a CU) takes the launches that
+// would need a second round of the pipelined one.  `allow_wide` = false leaves the
 // 256-column tile out.
 static int choose_tile(int M, int N, int K, bool allow_wide)
 {
     struct Tile { int bm, bn, R; float c0, u[3], f0, f1; };
-    static const Tile tiles[4] = {
+    static const Tile tiles[5] = {
         {64, 256, 2, 13.0f, {0.69f, 1.34f, 0.0f}, 0.0f, 1.22f},     // <2,2,3,0>
         {64, 128, 2, 6.0f, {0.39f, 0.69f, 0.0f}, 0.0f, 1.27f},      // <2,1,4,2> pipelined
         {32, 128, 3, 0.5f, {0.39f, 0.61f, 0.82f}, 0.35f, 0.92f},    // <1,1,4,2> pipelined
         {32, 128, 2, 4.0f, {0.27f, 0.46f, 0.0f}, 0.0f, 1.45f},      // <1,1,8,4> pipelined, deep prefetch
+        {64, 128, 3, 6.0f, {0.53f, 0.75f, 1.06f}, 0.0f, 1.3f},      // <2,1,3,0>, three workgroups per CU
     };
     const int G = (K + QUOTA_GROUP_W - 1) / QUOTA_GROUP_W;
     int best = -1;
     float best_t = 0.0f;
-    for (int i = allow_wide ? 0 : 1; i < 4; ++i) {
+    for (int i = allow_wide ? 0 : 1; i < 5; ++i) {
         const Tile &t = tiles[i];
         const long wgs = (long)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
         const float x = (float)wgs / (256.0f * t.R);
+        // a launch that spills into a second round pays for most of that round (measured: >= 1.6x)
+        const float over = t.f0 + t.f1 * x;
         const float est = x <= 1.0f ? t.c0 + G * t.u[(wgs + 255) / 256 - 1]
-                                    : t.c0 + G * t.u[t.R - 1] * (t.f0 + t.f1 * x);
+                                    : t.c0 + G * t.u[t.R - 1] * (i == 1 && over < 1.6f ? 1.6f : over);
         if (best < 0 || est < best_t) { best = i; best_t = est; }
     }
     return best;
@@ -480,7 +485,8 @@ extern "C" int quota_w4a4_gemm(const uint8_t *qa, const float *sa, int M, const 
     case 0: return launch<2, 2, 3, 0, false, false>(QUOTA_K_GEMM_64X256, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
     case 1: return launch<2, 1, 4, 2, true, false>(QUOTA_K_GEMM_64X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
     case 2: return launch<1, 1, 4, 2, true, false>(QUOTA_K_GEMM_32X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
-    default: return launch<1, 1, 8, 4, true, false>(QUOTA_K_GEMM_32X128_DEEP, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    case 3: return launch<1, 1, 8, 4, true, false>(QUOTA_K_GEMM_32X128_DEEP, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
+    default: return launch<2, 1, 3, 0, false, false, false, 3>(QUOTA_K_GEMM_64X128_LEAN, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
     }
 }
 
@@ -501,9 +507,9 @@ int quota_internal_w4a4_gemm_qkv(const uint8_t *qa, const float *sa, int M, cons
     f16 *y = (f16 *)y_opt;
     // (the 256-column tile is left out: with this epilogue it runs at its register limit)
     switch (choose_tile(M, W->N, W->K, false)) {
-    case 0: return launch<2, 2, 3, 0, false, false, true>(QUOTA_K_GEMM_64X256, qa, sa, M, W, y, 3 * d, nullptr, 0, nullptr, st, qe);
     case 1: return launch<2, 1, 4, 2, true, false, true>(QUOTA_K_GEMM_64X128, qa, sa, M, W, y, 3 * d, nullptr, 0, nullptr, st, qe);
     case 2: return launch<1, 1, 4, 2, true, false, true>(QUOTA_K_GEMM_32X128, qa, sa, M, W, y, 3 * d, nullptr, 0, nullptr, st, qe);
-    default: return launch<1, 1, 8, 4, true, false, true>(QUOTA_K_GEMM_32X128_DEEP, qa, sa, M, W, y, 3 * d, nullptr, 0, nullptr, st, qe);
+    case 3: return launch<1, 1, 8, 4, true, false, true>(QUOTA_K_GEMM_32X128_DEEP, qa, sa, M, W, y, 3 * d, nullptr, 0, nullptr, st, qe);
+    default: return launch<2, 1, 3, 0, false, false, true, 3>(QUOTA_K_GEMM_64X128_LEAN, qa, sa, M, W, y, 3 * d, nullptr, 0, nullptr, st, qe);
     }
 }

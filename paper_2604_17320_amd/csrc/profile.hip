@@ -6,7 +6,7 @@ QuotaProfiler g_quota_prof;
 
 static const char *const kKernelNames[QUOTA_KERNEL_COUNT] = {
     "quantize_act", "rmsnorm_quantize_act", "silu_mul_quantize_act", "w4a4_gemm_64x256",
-    "w4a4_gemm_64x128", "w4a4_gemm_32x128", "w4a4_gemm_32x128_deep", "w4a4_gemm_other", "rope_kv_quant", "kv_quant_append", "attention_fwd",
+    "w4a4_gemm_64x128", "w4a4_gemm_32x128", "w4a4_gemm_32x128_deep", "w4a4_gemm_64x128_lean", "w4a4_gemm_other", "rope_kv_quant", "kv_quant_append", "attention_fwd",
     "attention_colmass", "score_tokens", "topk_prune", "compact_rows", "quantize_weights",
     "pack_weights", "attention_decode", "kv_append_rows"};
 

@@ -22,6 +22,7 @@ import sys
 CLASSES = [
     ("w4a4_gemm_kernelILi2ELi2E", "w4a4_gemm_64x256"),
     ("w4a4_gemm_kernelILi2ELi1ELi4ELi2ELb1ELb0E", "w4a4_gemm_64x128"),
+    ("w4a4_gemm_kernelILi2ELi1ELi3ELi0ELb0ELb0E", "w4a4_gemm_64x128_lean"),
     ("w4a4_gemm_kernelILi1ELi1ELi4E", "w4a4_gemm_32x128"),
     ("w4a4_gemm_kernelILi1ELi1ELi8E", "w4a4_gemm_32x128_deep"),
     ("w4a4_gemm_kernel", "w4a4_gemm_other"),
