@@ -163,3 +163,20 @@ def test_layer_batched_serving_shape_sampled_sequence(qb):
         idx = got["keep_idx"][bb, :K]
         assert np.all(np.diff(idx) > 0) and idx.min() >= 0 and idx.max() < 576
         assert np.array_equal(got["rows"][bb, K:], np.arange(576, N))
+
+
+def test_layer_13b_high_resolution_shape(qb):
+    """One whole layer of the high-resolution 13B shape (d=5120, 40 heads, FFN 13824, 2880 visual + 64
+    text tokens, budget 766 = the schedule's first pruning layer), one sequence: teacher-forced
+    bit-exact and free-running within tolerance.  The largest N_v, N and FFN width the kernels meet."""
+    from test_gpu_layer import assert_teacher_forced_exact
+    shape = wl.Shape("c5_layer", d=5120, H=40, F=13824, layers=1, B=1, Nv=2880, Nt=64, n_outlier=51, vis_begin=0)
+    W, L, cos, sin = build_layer(shape, 0)
+    x, pos = wl.hidden_state(shape, 5), wl.positions(shape)
+    K = 766
+    ref = oracle.prefill_layer(W, x, pos, 1, shape.N, 0, shape.Nv, K, cos, sin, prune_mid=True)
+    got = run_gpu(qb, L, shape, x, pos, K, dict(o=ref["o"], z=ref["z"], cm_inter=ref["cm_inter"],
+                                                cm_intra=ref["cm_intra"]))
+    assert_teacher_forced_exact(ref, got, shape, K)
+    free = run_gpu(qb, L, shape, x, pos, K)
+    check_free_running(ref, free, shape, K)
