@@ -132,6 +132,53 @@ def serving_shape_kernels(shape, seed, reps=20):
     return dict(shape=f"batch {B} x {N} tokens, d={d}, F={F} ({M} rows)", reps=reps, kernels=out)
 
 
+def serving_decode(shape, stack, budgets, seed, steps=16):
+    """Batched-serving shape end to end on the same weights: batch 16 x (576 + 128) tokens pruned
+    prefill, then `steps` decode steps (random next-token embeddings) over the pruned 4-bit caches.
+    Supplementary: decode tokens/s and the weight-streaming bound of a step."""
+    import torch
+    from paper_2604_17320_amd import workloads as wl
+    from paper_2604_17320_amd.model import PrefillStack
+    B, Nv, Nt = 16, shape.Nv, 128
+    N = Nv + Nt
+    big = PrefillStack(stack.layers, B, N, 0, Nv, budgets, decode_capacity=steps + 3)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed + 99)
+    x0 = torch.randn((B * N, shape.d), generator=g, device="cuda", dtype=torch.float32).to(torch.float16)
+    pos0 = torch.arange(N, dtype=torch.int32, device="cuda").repeat(B)
+    big.run(x0, pos0)                           # warm-up
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    big.run(x0, pos0)
+    torch.cuda.synchronize()
+    prefill_ms = (time.perf_counter() - t0) * 1e3
+    xs = torch.randn((steps + 1, B, shape.d), generator=g, device="cuda", dtype=torch.float32).to(torch.float16)
+    pn = torch.full((B,), N, dtype=torch.int32, device="cuda")
+    big.decode(xs[0], pn)                       # warm-up step (also grows every cache by one row)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        pn = torch.full((B,), N + 1 + i, dtype=torch.int32, device="cuda")
+        big.decode(xs[1 + i], pn)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    from paper_2604_17320_amd import binding as qb
+    qb.quota_profile_begin(20 * len(stack.layers) + 16)
+    big.decode(xs[0], torch.full((B,), N + 1 + steps, dtype=torch.int32, device="cuda"))
+    kstats = qb.quota_profile_collect()
+    gpu_ms = sum(v["total_ms"] for v in kstats.values())
+    per_kernel = {k: round(v["total_ms"] * 1e3 / v["launches"], 2) for k, v in kstats.items()}
+    wbytes = sum(l.weight_bytes() for l in stack.layers)
+    kv_bytes = sum(B * c.len * (shape.d + shape.d // 16) for c in big.caches)
+    return dict(shape=f"batch {B} x ({Nv} + {Nt}) tokens, {len(stack.layers)} layers", prefill_ms=round(prefill_ms, 2),
+                prefill_tokens_per_s=round(B * N / prefill_ms * 1e3, 1), decode_steps=steps,
+                decode_ms_per_step=round(ms, 3), decode_tokens_per_s=round(B / ms * 1e3, 1),
+                decode_kernel_ms_per_step=round(gpu_ms, 3), decode_avg_us_per_kernel=per_kernel,
+                weight_bytes_per_step=wbytes, kv_bytes_per_step=kv_bytes,
+                hbm_bound_ms=round((wbytes + kv_bytes) / (PEAK_HBM_GBS * 1e9) * 1e3, 3),
+                frac_hbm_peak=round((wbytes + kv_bytes) / (ms * 1e-3) / (PEAK_HBM_GBS * 1e9), 4))
+
+
 def cpu_baseline(shape, stack, budgets, rope, sample_layers, seed):
     """The oracle, as it stands, on a bounded sample: a few layers of the stack, each fed a
     synthetic hidden state with the row count that layer sees in the real run."""
@@ -305,6 +352,8 @@ def main():
                kernels=kern)
     if not args.no_serving_shape:
         out["serving_shape_kernels"] = serving_shape_kernels(shape, args.seed)
+        if args.config == "c3":
+            out["serving_decode"] = serving_decode(shape, stack, budgets, args.seed)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(shape, stack, budgets, rope, sample_layers, args.seed)
     print(json.dumps(out))

@@ -309,6 +309,16 @@ int quota_make_recipe(const double *S, int m, double tau, double p_min, int V0,
                       double *s_norm_opt, double *pi_opt, double *r_out,
                       int32_t *K_out);
 
+/* GFLOPs ratio (percent) of a pruning recipe against the unpruned model
+ * (GFLOPs-estimation appendix): (F_vt + F_pj + sum_l C(T + V_hat[l])) /
+ * (F_vt + F_pj + L C(T + V0)), with the per-layer cost of a LLaMA-style block
+ * C(S) = 2 S (4 d^2 + 3 d F) + 4 S^2 d (the appendix names the projection/MLP
+ * and attention terms but prints no formula; this is the usual count, 2 FLOPs
+ * per multiply-add, attention in full).  V_hat[L] (host) = visual tokens
+ * executed by each layer; T = text-length proxy. */
+int quota_gflops_ratio(const int32_t *V_hat, int L, int V0, int T, int d, int F,
+                       double F_vt, double F_pj, double *ratio_percent);
+
 /* ---- decode over the pruned 4-bit KV cache ------------------------------- */
 
 /* Single-query attention of one new token per sequence over `cache` (deployment

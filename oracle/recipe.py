@@ -70,3 +70,19 @@ def make_recipe(S, tau: float, p_min: float, V0: int):
     pi = layer_shares(s_norm, tau)
     r = keep_schedule(pi, p_min)
     return dict(s_norm=s_norm, pi=pi, r=r, K=budgets(r, V0))
+
+
+def layer_cost(S: int, d: int, F: int) -> float:
+    """C_l as a function of the executed sequence length S = T + V_l (GFLOPs-estimation appendix).
+    The paper names the two terms but prints no formula; the reading used here is the usual count
+    for a LLaMA-style block, 2 FLOPs per multiply-add: token-wise projections and SwiGLU MLP
+    2 S (4 d^2 + 3 d F), attention scores and values 4 S^2 d (full, not causal-halved)."""
+    return 2.0 * S * (4.0 * d * d + 3.0 * d * F) + 4.0 * float(S) * S * d
+
+
+def gflops_ratio(V_hat, V0: int, T: int, d: int, F: int, F_vt: float = 0.0, F_pj: float = 0.0) -> float:
+    """GFLOPs ratio (percent) of a pruning recipe: (F_VT + F_PJ + sum_l C_l(V_l, T)) over the same with
+    V_l = V0 in every layer.  V_hat[l] = visual tokens executed by layer l."""
+    pruned = F_vt + F_pj + sum(layer_cost(T + int(v), d, F) for v in V_hat)
+    base = F_vt + F_pj + len(V_hat) * layer_cost(T + V0, d, F)
+    return 100.0 * pruned / base

@@ -236,6 +236,15 @@ def quota_make_recipe(S, tau: float, p_min: float, V0: int):
     return dict(s_norm=list(sn), pi=list(pi), r=list(r), K=list(K))
 
 
+def quota_gflops_ratio(V_hat, V0: int, T: int, d: int, F: int, F_vt: float = 0.0, F_pj: float = 0.0) -> float:
+    L = len(V_hat)
+    v = (C.c_int32 * L)(*[int(x) for x in V_hat])
+    out = C.c_double(0.0)
+    _check(lib().quota_gflops_ratio(v, L, int(V0), int(T), int(d), int(F), C.c_double(F_vt), C.c_double(F_pj),
+                                    C.byref(out)), "quota_gflops_ratio")
+    return out.value
+
+
 def quota_attention_decode(q, cache: KVCache, o):
     _check(lib().quota_attention_decode(_ptr(q, torch.float16), C.byref(cache), _ptr(o, torch.float16), _stream()),
            "quota_attention_decode")

@@ -69,3 +69,26 @@ extern "C" int quota_make_recipe(const double *S, int m, double tau, double p_mi
     }
     return QUOTA_OK;
 }
+
+// GFLOPs ratio of a recipe (GFLOPs-estimation appendix): C_l(S) = 2 S (4 d^2 + 3 d F) + 4 S^2 d
+// with S = T + V_l, 2 FLOPs per multiply-add, attention counted in full.
+static double layer_cost(double S, double d, double F)
+{
+    return 2.0 * S * (4.0 * d * d + 3.0 * d * F) + 4.0 * S * S * d;
+}
+
+extern "C" int quota_gflops_ratio(const int32_t *V_hat, int L, int V0, int T, int d, int F, double F_vt,
+                                  double F_pj, double *ratio_percent)
+{
+    if (!V_hat || !ratio_percent) return QUOTA_ERR_NULL;
+    if (L <= 0 || V0 < 0 || T < 0 || d <= 0 || F <= 0 || !(F_vt >= 0.0) || !(F_pj >= 0.0))
+        return QUOTA_ERR_INVALID_ARG;
+    double pruned = F_vt + F_pj, base = F_vt + F_pj + (double)L * layer_cost((double)T + V0, d, F);
+    for (int l = 0; l < L; ++l) {
+        if (V_hat[l] < 0) return QUOTA_ERR_INVALID_ARG;
+        pruned += layer_cost((double)T + V_hat[l], d, F);
+    }
+    if (base <= 0.0) return QUOTA_ERR_INVALID_ARG;
+    *ratio_percent = 100.0 * pruned / base;
+    return QUOTA_OK;
+}

@@ -86,6 +86,10 @@ def test_recipe_matches_the_oracle():
         for k_got, k_ref, r in zip(got["K"], ref["K"], ref["r"]):
             assert k_got == k_ref or abs(r * V0 - round(r * V0)) < 1e-6      # equal unless r V0 sits on an integer
         assert all(a >= b for a, b in zip(got["K"], got["K"][1:])) and got["K"][-1] >= int(np.ceil(p_min * V0 - 1e-9))
+    sched = wl.schedule_for(wl.CONFIGS[2])
+    assert binding.quota_gflops_ratio(sched, 576, 64, 4096, 11008) == pytest.approx(
+        oracle.recipe.gflops_ratio(sched, 576, 64, 4096, 11008), rel=1e-13)
+    assert binding.quota_gflops_ratio([576] * 4, 576, 64, 4096, 11008, 1e12, 1e9) == 100.0
     flat = binding.quota_make_recipe([0.2, 0.2, 0.2], 1.0, 0.3, 576)
     assert flat["s_norm"] == [0.5, 0.5, 0.5] and flat["K"][-1] == 173
     a = wl.rng(5, "n").uniform(0.1, 1, 8).tolist()

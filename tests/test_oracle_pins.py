@@ -566,3 +566,23 @@ def test_recipe_eq4_eq5_schedule_and_budgets(golden_dir):
     assert rec.budgets([1.0, 0.0, 0.25, 0.1], 580).tolist() == [580, 0, 145, 58]  # integers are not bumped
     full = rec.make_recipe(np.array([1.0, 2.0, 3.0, 4.0, 5.0]), 1.0, 0.3, 576)
     assert np.allclose(full["s_norm"], [0.1, 0.1875, 0.5, 0.8125, 0.9]) and full["K"][-1] == 173
+
+
+def test_gflops_ratio_closed_forms():
+    rec = oracle.recipe
+    d, F, V0, T, L = 4096, 11008, 576, 64, 32
+    assert rec.gflops_ratio([V0] * L, V0, T, d, F) == 100.0                      # nothing pruned
+    # everything pruned in every layer: only the text tokens run
+    assert rec.gflops_ratio([0] * L, V0, T, d, F) == pytest.approx(100.0 * rec.layer_cost(T, d, F) / rec.layer_cost(T + V0, d, F))
+    # one layer of S tokens against the hand count 2 S (4 d^2 + 3 d F) + 4 S^2 d
+    assert rec.layer_cost(10, 8, 16) == 2 * 10 * (4 * 64 + 3 * 8 * 16) + 4 * 100 * 8
+    # pruning earlier saves more than pruning later with the same final count (the appendix's remark)
+    early = [V0] * 2 + [173] * 30
+    late = [V0] * 16 + [173] * 16
+    assert rec.gflops_ratio(early, V0, T, d, F) < rec.gflops_ratio(late, V0, T, d, F) < 100.0
+    # a constant vision-tower / projector term only pulls the ratio towards 100 %
+    assert rec.gflops_ratio(early, V0, T, d, F, F_vt=1e12) > rec.gflops_ratio(early, V0, T, d, F)
+    # the cost is dominated by the token-wise term at these lengths: ratio close to the token ratio
+    r = rec.gflops_ratio(early, V0, T, d, F)
+    tok = 100.0 * (2 * (V0 + T) + 30 * (173 + T)) / (32 * (V0 + T))
+    assert abs(r - tok) < 1.5
