@@ -357,7 +357,7 @@ enum {
     QUOTA_K_GEMM_OTHER, QUOTA_K_ROPE_KV_QUANT,
     QUOTA_K_KV_QUANT_APPEND, QUOTA_K_ATTENTION_FWD, QUOTA_K_ATTENTION_COLMASS,
     QUOTA_K_SCORE_TOKENS, QUOTA_K_TOPK_PRUNE, QUOTA_K_COMPACT_ROWS, QUOTA_K_QUANTIZE_WEIGHTS,
-    QUOTA_K_PACK_WEIGHTS, QUOTA_K_ATTENTION_DECODE, QUOTA_K_KV_APPEND_ROWS, QUOTA_KERNEL_COUNT
+    QUOTA_K_PACK_WEIGHTS, QUOTA_K_ATTENTION_DECODE, QUOTA_K_KV_APPEND_ROWS, QUOTA_K_GEMM_ROWS16, QUOTA_KERNEL_COUNT
 };
 
 /* Per kernel class: launches seen, summed HIP-event time around them (ms) and

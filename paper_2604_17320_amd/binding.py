@@ -62,7 +62,7 @@ class KernelStat(C.Structure):
     _fields_ = [("launches", C.c_long), ("total_ms", C.c_double), ("ops", C.c_double), ("bytes", C.c_double)]
 
 
-KERNEL_COUNT = 20
+KERNEL_COUNT = 21
 
 _lib = None
 

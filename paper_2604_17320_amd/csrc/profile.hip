@@ -8,7 +8,7 @@ static const char *const kKernelNames[QUOTA_KERNEL_COUNT] = {
     "quantize_act", "rmsnorm_quantize_act", "silu_mul_quantize_act", "w4a4_gemm_64x256",
     "w4a4_gemm_64x128", "w4a4_gemm_32x128", "w4a4_gemm_32x128_deep", "w4a4_gemm_64x128_lean", "w4a4_gemm_other", "rope_kv_quant", "kv_quant_append", "attention_fwd",
     "attention_colmass", "score_tokens", "topk_prune", "compact_rows", "quantize_weights",
-    "pack_weights", "attention_decode", "kv_append_rows"};
+    "pack_weights", "attention_decode", "kv_append_rows", "w4a4_gemm_rows16"};
 
 extern "C" const char *quota_kernel_name(int kernel_id)
 {

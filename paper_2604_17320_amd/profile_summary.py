@@ -26,6 +26,7 @@ CLASSES = [
     ("w4a4_gemm_kernelILi1ELi1ELi4E", "w4a4_gemm_32x128"),
     ("w4a4_gemm_kernelILi1ELi1ELi8E", "w4a4_gemm_32x128_deep"),
     ("w4a4_gemm_kernel", "w4a4_gemm_other"),
+    ("w4a4_gemv16_kernel", "w4a4_gemm_rows16"),
     ("silu_mul_quantize_act_kernel", "silu_mul_quantize_act"),
     ("rmsnorm_quantize_act_kernel", "rmsnorm_quantize_act"),
     ("quantize_act_kernel", "quantize_act"),

@@ -176,7 +176,8 @@ def _pack4(codes):
 
 
 @pytest.mark.parametrize("M,N,K", [(80, 1536, 512), (35, 512, 1376), (300, 2752, 512), (129, 4096, 4096),
-                                   (1, 64, 32), (640, 1536, 1376), (257, 320, 11008)])
+                                   (1, 64, 32), (640, 1536, 1376), (257, 320, 11008),
+                                   (16, 4096, 4096), (7, 512, 1376), (16, 9216, 512), (13, 128, 11008)])
 def test_w4a4_gemm_bit_exact(qb, M, N, K):
     from paper_2604_17320_amd.model import PackedLinear
     qa, sa, qw, sw, res = _gemm_case(M, N, K, 21)
