@@ -10,10 +10,18 @@ namespace {
 
 constexpr int DEC_LMAX = 8192;      // cached rows one workgroup can softmax over (scores live in LDS)
 
-// sign-extended code e (0..7) of a packed dword
-__device__ __forceinline__ float code_at(uint32_t w, int e)
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+
+// Dequantizes codes e and e+4 (e = 0..3) of a packed dword to x_hat = fp16(code * s) as a half
+// pair.  wx = w ^ 0x88888888 turns each two's-complement nibble c into c + 8 in [0, 15];
+// 0x6400 | (c + 8) is the fp16 number 1024 + c + 8, so subtracting 1032 leaves the code exactly,
+// and the fp16 multiply rounds code * s once, to nearest -- the value the quantizer defines.
+__device__ __forceinline__ h2 dequant_pair(uint32_t wx, int e, h2 s2)
 {
-    return (float)(((int)(w << (28 - 4 * e))) >> 28);
+    const uint32_t bits = ((wx >> (4 * e)) & 0x000F000Fu) | 0x64006400u;
+    h2 c = __builtin_bit_cast(h2, bits);
+    c = c - h2{(_Float16)1032.0f, (_Float16)1032.0f};
+    return c * s2;
 }
 
 // Moves the B freshly quantized K/V rows (staged, dense) to row `len` of each sequence.
@@ -49,13 +57,16 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
     constexpr int WPT = DH / 8;             // packed dwords per token and head
     constexpr int GPT = DH / 64;            // scale groups per token and head
     constexpr int TL = 256 / WPT;           // token lanes of pass 2
-    __shared__ float qs[DH];
+    __shared__ h2 qp[DH / 2];               // q as pairs: qp[4 i + e] = (q[8 i + e], q[8 i + e + 4])
     __shared__ float sc[DEC_LMAX];
     __shared__ float red[TL * DH];
     __shared__ float wred[8];
     const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const int n32 = d >> 3, ng = d >> 6;
-    if (tid < DH) qs[tid] = (float)q[(size_t)b * d + h * DH + tid];
+    if (tid < DH / 2) {
+        const f16 *qh = q + (size_t)b * d + h * DH + 8 * (tid >> 2) + (tid & 3);
+        qp[tid] = h2{qh[0], qh[4]};
+    }
     __syncthreads();
     const float scale = 1.0f / sqrtf((float)DH);
 
@@ -67,18 +78,19 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
         float dot = 0.0f;
 #pragma unroll
         for (int g = 0; g < GPT; ++g) {
-            const float s = (float)sp[g];
+            const _Float16 sh = sp[g];
+            const h2 s2 = h2{sh, sh};
 #pragma unroll
             for (int w4 = 0; w4 < 2; ++w4) {
                 const uint4 pk = *reinterpret_cast<const uint4 *>(kw + 8 * g + 4 * w4);
-                const uint32_t ww[4] = {pk.x, pk.y, pk.z, pk.w};
+                const uint32_t ww[4] = {pk.x ^ 0x88888888u, pk.y ^ 0x88888888u, pk.z ^ 0x88888888u,
+                                        pk.w ^ 0x88888888u};
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float kh = (float)(f16)(code_at(ww[i], e) * s);
-                        dot = fmaf(qs[64 * g + 32 * w4 + 8 * i + e], kh, dot);
-                    }
+                    for (int e = 0; e < 4; ++e)     // channels (8i + e, 8i + e + 4) of this 32-channel piece
+                        dot = __builtin_amdgcn_fdot2(qp[(64 * g + 32 * w4 + 8 * i) / 2 + e],
+                                                     dequant_pair(ww[i], e, s2), dot, false);
             }
         }
         dot *= scale;
@@ -105,20 +117,28 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
     constexpr int UN = 8;                   // tokens in flight per thread: loads first, then the math
     for (int t0 = tl; t0 < L; t0 += TL * UN) {
         uint32_t w[UN];
-        float sv[UN], pv[UN];
+        f16 sv[UN];
+        float pv[UN];
 #pragma unroll
         for (int i = 0; i < UN; ++i) {
             const int t = t0 + TL * i;
             const bool ok = t < L;
             const size_t row = (size_t)b * capacity + (ok ? t : 0);
             w[i] = vc[row * n32 + h * WPT + cl];
-            sv[i] = (float)vs[row * ng + h * GPT + (cl >> 3)];
+            sv[i] = vs[row * ng + h * GPT + (cl >> 3)];
             pv[i] = ok ? sc[t] : 0.0f;
         }
 #pragma unroll
-        for (int i = 0; i < UN; ++i)
+        for (int i = 0; i < UN; ++i) {
+            const uint32_t wx = w[i] ^ 0x88888888u;
+            const h2 s2 = h2{sv[i], sv[i]};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] = fmaf(pv[i], (float)(f16)(code_at(w[i], e) * sv[i]), acc[e]);
+            for (int e = 0; e < 4; ++e) {
+                const h2 vh = dequant_pair(wx, e, s2);
+                acc[e] = fmaf(pv[i], (float)vh[0], acc[e]);
+                acc[e + 4] = fmaf(pv[i], (float)vh[1], acc[e + 4]);
+            }
+        }
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) red[tl * DH + 8 * cl + e] = acc[e];
