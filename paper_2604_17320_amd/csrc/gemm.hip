@@ -364,8 +364,9 @@ __global__ __launch_bounds__(256, WPE) void w4a4_gemm_kernel(
                         uint32_t *codes = region == 1 ? qe.k_codes : qe.v_codes;
                         f16 *scales = region == 1 ? qe.k_scales : qe.v_scales;
                         *reinterpret_cast<uint4 *>(xh + (size_t)m * d + col) = hat.u;
-                        codes[(size_t)m * cpr + (col >> 3)] = word;
-                        if ((c & 7) == 0) scales[(size_t)m * gpr + (col >> 6)] = sc;
+                        const size_t orow = (size_t)m * qe.code_row_stride + qe.code_row_offset;
+                        codes[orow * cpr + (col >> 3)] = word;
+                        if ((c & 7) == 0) scales[orow * gpr + (col >> 6)] = sc;
                     }
                 }
             }

@@ -53,6 +53,7 @@ struct quota_qkv_epilogue {
     f16 *q_rot, *khat, *vhat;
     uint32_t *k_codes, *v_codes;
     f16 *k_scales, *v_scales;
+    long code_row_stride, code_row_offset;   // codes / scales of token row m go to row m * stride + offset
 };
 int quota_internal_w4a4_gemm_qkv(const uint8_t *qa, const float *sa, int M, const quota_weights *W,
                                  void *y_opt, const quota_qkv_epilogue *qe, hipStream_t st);

@@ -95,7 +95,7 @@ int dump(void *dst, const void *src, size_t bytes, hipStream_t st)
 // the stand-alone RoPE/KV kernel.  Both give the same bits.  want_qkv: also keep the plain
 // projection output in w.qkv.
 static int qkv_rope_kv_quant(const quota_layer *L, const LayerWs &w, int M, const int32_t *pos,
-                             bool want_qkv, hipStream_t st)
+                             bool want_qkv, hipStream_t st, quota_kv_cache *append_to = nullptr)
 {
     const int d = L->H * L->dh;
     quota_qkv_epilogue qe;
@@ -103,11 +103,21 @@ static int qkv_rope_kv_quant(const quota_layer *L, const LayerWs &w, int M, cons
     qe.q_rot = w.q_rot; qe.khat = w.khat; qe.vhat = w.vhat;
     qe.k_codes = (uint32_t *)w.skc; qe.v_codes = (uint32_t *)w.svc;
     qe.k_scales = w.sks; qe.v_scales = w.svs;
+    qe.code_row_stride = 1; qe.code_row_offset = 0;
+    if (append_to) {        // decode: row b is sequence b's new token; its K/V go straight to cache row len
+        qe.k_codes = (uint32_t *)append_to->k_codes; qe.v_codes = (uint32_t *)append_to->v_codes;
+        qe.k_scales = (f16 *)append_to->k_scales; qe.v_scales = (f16 *)append_to->v_scales;
+        qe.code_row_stride = append_to->capacity; qe.code_row_offset = append_to->len;
+    }
     int rc = quota_internal_w4a4_gemm_qkv(w.qa, w.sa, M, &L->qkv, want_qkv ? w.qkv : nullptr, &qe, st);
-    if (rc != QUOTA_ERR_SHAPE) return rc;
+    if (rc != QUOTA_ERR_SHAPE) {
+        if (rc == QUOTA_OK && append_to) append_to->len += 1;
+        return rc;
+    }
     TRY(quota_w4a4_gemm(w.qa, w.sa, M, &L->qkv, w.qkv, 3 * d, nullptr, 0, nullptr, st));
-    return quota_rope_kv_quant(w.qkv, M, L->H, L->dh, pos, L->cosT, L->sinT, L->n_pos, w.q_rot, w.khat,
-                               w.vhat, w.skc, w.sks, w.svc, w.svs, st);
+    TRY(quota_rope_kv_quant(w.qkv, M, L->H, L->dh, pos, L->cosT, L->sinT, L->n_pos, w.q_rot, w.khat,
+                            w.vhat, w.skc, w.sks, w.svc, w.svs, st));
+    return append_to ? quota_internal_kv_append_rows(d, w.skc, w.sks, w.svc, w.svs, append_to, st) : QUOTA_OK;
 }
 
 extern "C" size_t quota_prefill_workspace_bytes(const quota_layer *L, int B, int N)
@@ -240,11 +250,11 @@ extern "C" int quota_decode_layer(const quota_layer *L, const void *x_f16, const
 
     TRY(quota_rmsnorm_quantize_act(x_f16, B, d, d, L->gamma1, L->eps, w.qa, w.sa, nullptr, nullptr,
                                    nullptr, st));
-    TRY(qkv_rope_kv_quant(L, w, B, pos, t->qkv != nullptr, st));
+    // the new token's K/V join the cache first (written by the QKV epilogue itself, or by the
+    // append kernel on the unfused path); attention then reads all of it in 4-bit form
+    TRY(qkv_rope_kv_quant(L, w, B, pos, t->qkv != nullptr, st, cache));
     TRY(dump(t->qkv, w.qkv, (size_t)B * 3 * d * 2, st));
     TRY(dump(t->q_rot, w.q_rot, (size_t)B * d * 2, st));
-    // the new token's K/V join the cache first; attention then reads all of it in 4-bit form
-    TRY(quota_internal_kv_append_rows(d, w.skc, w.sks, w.svc, w.svs, cache, st));
     TRY(quota_attention_decode(w.q_rot, cache, w.o, st));
     TRY(dump(t->o, w.o, (size_t)B * d * 2, st));
     const f16 *o_used = t->inject_o ? (const f16 *)t->inject_o : w.o;
