@@ -144,17 +144,20 @@ def kv_quant(x, g: int = GROUP_KV):
 
 
 def attention(q, khat, vhat, B: int, N: int, H: int, dh: int, vis_begin: int, Nv: int,
-              want_P: bool = False):
-    """q/khat/vhat fp16 [B*N, H*dh] -> (o fp16, cm_inter f32 [B,Nv], cm_intra f32 [B,Nv])."""
+              want_P: bool = False, Hkv: int = None):
+    """q fp16 [B*N, H*dh], khat/vhat fp16 [B*N, Hkv*dh] (Hkv = H unless given: grouped-query
+    attention, query head h reads K/V head h // (H // Hkv)) ->
+    (o fp16, cm_inter f32 [B,Nv], cm_intra f32 [B,Nv]); the cues average over the H query heads."""
+    Hkv = H if Hkv is None else Hkv
     q = _c(q, np.float16)
     khat = _c(khat, np.float16)
     vhat = _c(vhat, np.float16)
-    assert q.shape == (B * N, H * dh)
+    assert q.shape == (B * N, H * dh) and khat.shape == (B * N, Hkv * dh) == vhat.shape and H % Hkv == 0
     o = np.empty_like(q)
     ci = np.zeros((B, Nv), np.float32)
     cv = np.zeros((B, Nv), np.float32)
     P = np.empty((B, H, N, N), np.float64) if want_P else None
-    lib().orc_attention(_p(q), _p(khat), _p(vhat), B, N, H, dh, vis_begin, Nv,
+    lib().orc_attention(_p(q), _p(khat), _p(vhat), B, N, H, Hkv, dh, vis_begin, Nv,
                         _p(o), _p(ci), _p(cv), _p(P))
     return (o, ci, cv, P) if want_P else (o, ci, cv)
 

@@ -31,6 +31,11 @@ class LayerWeights:
     H: int
     dh: int
     F: int
+    Hkv: int = None     # K/V heads (grouped-query attention); None = H.  qkv then has (H + 2 Hkv) dh rows
+
+    @property
+    def kv_heads(self) -> int:
+        return self.H if self.Hkv is None else self.Hkv
 
 
 def kept_rows(keep_idx, B, N, vis_begin, Nv):
@@ -73,12 +78,13 @@ def prefill_layer(W: LayerWeights, x, pos, B, N, vis_begin, Nv, K, cos, sin,
     h1 = rmsnorm(x, W.gamma1, W.eps)
     qa1, sa1, _, _ = quantize_act(h1)
     qkv = w4a4_gemm(qa1, sa1, *W.qkv)
+    dkv = W.kv_heads * W.dh
     q = rope(qkv[:, :d], W.H, W.dh, pos, cos, sin)
-    k = rope(qkv[:, d:2 * d], W.H, W.dh, pos, cos, sin)
-    v = np.ascontiguousarray(qkv[:, 2 * d:])
+    k = rope(qkv[:, d:d + dkv], W.kv_heads, W.dh, pos, cos, sin)
+    v = np.ascontiguousarray(qkv[:, d + dkv:])
     kc, ks, khat = kv_quant(k)
     vc, vs, vhat = kv_quant(v)
-    o, cm_inter, cm_intra = attention(q, khat, vhat, B, N, W.H, W.dh, vis_begin, Nv)
+    o, cm_inter, cm_intra = attention(q, khat, vhat, B, N, W.H, W.dh, vis_begin, Nv, Hkv=W.kv_heads)
     if inject:
         o = inject.get("o", o)
         cm_inter = inject.get("cm_inter", cm_inter)
@@ -132,7 +138,7 @@ def dequant_kv(codes, scales, g: int = 64):
     return (np.asarray(codes, np.int8).astype(np.float32) * s).astype(np.float16)
 
 
-def decode_attention(q, kc, ks, vc, vs, H: int, dh: int):
+def decode_attention(q, kc, ks, vc, vs, H: int, dh: int, Hkv: int = None):
     """Single-query attention of one new token per sequence over its 4-bit cache.
 
     q fp16 [B, H*dh] (rotated); kc/vc int8 [B, L, H*dh]; ks/vs fp16 [B, L, H*dh/64];
@@ -143,16 +149,18 @@ def decode_attention(q, kc, ks, vc, vs, H: int, dh: int):
     """
     from . import f64_to_f16
     B, L, D = kc.shape
-    khat = dequant_kv(kc, ks).astype(np.float64).reshape(B, L, H, dh)
-    vhat = dequant_kv(vc, vs).astype(np.float64).reshape(B, L, H, dh)
+    Hkv = H if Hkv is None else Hkv
+    rep = H // Hkv                      # query head h reads K/V head h // rep
+    khat = dequant_kv(kc, ks).astype(np.float64).reshape(B, L, Hkv, dh)
+    vhat = dequant_kv(vc, vs).astype(np.float64).reshape(B, L, Hkv, dh)
     qf = np.asarray(q, np.float16).astype(np.float64).reshape(B, H, dh)
     o = np.zeros((B, H, dh), np.float64)
     for b in range(B):
         for h in range(H):
-            s = khat[b, :, h, :] @ qf[b, h] / np.sqrt(float(dh))
+            s = khat[b, :, h // rep, :] @ qf[b, h] / np.sqrt(float(dh))
             p = np.exp(s - s.max())
             p /= p.sum()
-            o[b, h] = p @ vhat[b, :, h, :]
+            o[b, h] = p @ vhat[b, :, h // rep, :]
     return f64_to_f16(o.reshape(B, H * dh))
 
 
@@ -175,16 +183,17 @@ def decode_layer(W: LayerWeights, x, pos, cache, cos, sin, inject=None):
     h1 = rmsnorm(x, W.gamma1, W.eps)
     qa1, sa1, _, _ = quantize_act(h1)
     qkv = w4a4_gemm(qa1, sa1, *W.qkv)
+    dkv = W.kv_heads * W.dh
     q = rope(qkv[:, :d], W.H, W.dh, pos, cos, sin)
-    k = rope(qkv[:, d:2 * d], W.H, W.dh, pos, cos, sin)
-    v = np.ascontiguousarray(qkv[:, 2 * d:])
+    k = rope(qkv[:, d:d + dkv], W.kv_heads, W.dh, pos, cos, sin)
+    v = np.ascontiguousarray(qkv[:, d + dkv:])
     kc, ks, _ = kv_quant(k)
     vc, vs, _ = kv_quant(v)
     grown = dict(kc=np.concatenate([cache["kc"], kc[:, None, :]], axis=1),
                  ks=np.concatenate([cache["ks"], ks[:, None, :]], axis=1),
                  vc=np.concatenate([cache["vc"], vc[:, None, :]], axis=1),
                  vs=np.concatenate([cache["vs"], vs[:, None, :]], axis=1))
-    o = decode_attention(q, grown["kc"], grown["ks"], grown["vc"], grown["vs"], W.H, W.dh)
+    o = decode_attention(q, grown["kc"], grown["ks"], grown["vc"], grown["vs"], W.H, W.dh, W.kv_heads)
     if inject and "o" in inject:
         o = inject["o"]
     qa2, sa2, _, _ = quantize_act(o)

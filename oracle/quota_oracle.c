@@ -305,11 +305,14 @@ void orc_kv_quant(const uint16_t *x, int M, int Hdh, long ldx, int g,
  * q, khat, vhat, o are [B][N][H][dh] dense.  cm_* are [B][Nv] fp32.
  * P_opt (tests only) receives [B][H][N][N] fp64 probabilities. */
 void orc_attention(const uint16_t *q, const uint16_t *khat,
-                   const uint16_t *vhat, int B, int N, int H, int dh,
+                   const uint16_t *vhat, int B, int N, int H, int Hkv, int dh,
                    int vis_begin, int Nv, uint16_t *o, float *cm_inter,
                    float *cm_intra, double *P_opt)
 {
-    size_t d = (size_t)H * dh;
+    /* grouped-query attention: query head h reads K/V head h / (H / Hkv); Hkv == H is
+     * ordinary multi-head attention.  q, o have H heads per row, khat, vhat have Hkv. */
+    size_t d = (size_t)H * dh, dkv = (size_t)Hkv * dh;
+    int rep = H / Hkv;
     double inv_sqrt = 1.0 / sqrt((double)dh);
     /* per (b, h) column sums, reduced over heads afterwards in head order */
     double *ci = (double *)calloc((size_t)B * H * (Nv > 0 ? Nv : 1), sizeof(double));
@@ -325,7 +328,7 @@ void orc_attention(const uint16_t *q, const uint16_t *khat,
                 const uint16_t *qi = q + ((size_t)b * N + i) * d + (size_t)h * dh;
                 double mx = -INFINITY;
                 for (int j = 0; j <= i; ++j) {
-                    const uint16_t *kj = khat + ((size_t)b * N + j) * d + (size_t)h * dh;
+                    const uint16_t *kj = khat + ((size_t)b * N + j) * dkv + (size_t)(h / rep) * dh;
                     double s = 0.0;
                     for (int c = 0; c < dh; ++c) s += (double)h2f(qi[c]) * (double)h2f(kj[c]);
                     s *= inv_sqrt;
@@ -338,7 +341,7 @@ void orc_attention(const uint16_t *q, const uint16_t *khat,
                 int q_is_vis = (i >= vis_begin && i < vis_begin + Nv);
                 for (int j = 0; j <= i; ++j) {
                     double pj = p[j] / den;
-                    const uint16_t *vj = vhat + ((size_t)b * N + j) * d + (size_t)h * dh;
+                    const uint16_t *vj = vhat + ((size_t)b * N + j) * dkv + (size_t)(h / rep) * dh;
                     for (int c = 0; c < dh; ++c) acc[c] += pj * (double)h2f(vj[c]);
                     if (j >= vis_begin && j < vis_begin + Nv) {
                         if (q_is_vis) cvh[j - vis_begin] += pj;

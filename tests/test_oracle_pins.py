@@ -586,3 +586,57 @@ def test_gflops_ratio_closed_forms():
     r = rec.gflops_ratio(early, V0, T, d, F)
     tok = 100.0 * (2 * (V0 + T) + 30 * (173 + T)) / (32 * (V0 + T))
     assert abs(r - tok) < 1.5
+
+
+# ---- grouped-query attention (the Qwen2.5-VL shape of the paper's second model) ---------------
+
+def test_gqa_attention_equals_mha_with_replicated_kv_heads():
+    """Grouped-query attention is multi-head attention in which every K/V head serves a group of
+    query heads: replicating the K/V heads must give the already pinned multi-head result."""
+    r = wl.rng(21, "gqa")
+    B, N, H, Hkv, dh, vb, Nv = 2, 19, 6, 2, 64, 2, 11
+    q = r.standard_normal((B * N, H * dh)).astype(np.float16)
+    _, _, khat = oracle.kv_quant(r.standard_normal((B * N, Hkv * dh)).astype(np.float16))
+    _, _, vhat = oracle.kv_quant(r.standard_normal((B * N, Hkv * dh)).astype(np.float16))
+    o, ci, cv = oracle.attention(q, khat, vhat, B, N, H, dh, vb, Nv, Hkv=Hkv)
+    rep = lambda a: np.repeat(a.reshape(B * N, Hkv, dh), H // Hkv, axis=1).reshape(B * N, H * dh)
+    o2, ci2, cv2 = oracle.attention(q, rep(khat), rep(vhat), B, N, H, dh, vb, Nv)
+    assert np.array_equal(o, o2) and np.array_equal(ci, ci2) and np.array_equal(cv, cv2)
+    # and the decode read of the same rows
+    kc, ks, _ = oracle.kv_quant(khat)
+    vc, vs, _ = oracle.kv_quant(vhat)
+    sh = lambda a: a.reshape(B, N, -1)
+    d1 = oracle.decode_attention(q.reshape(B, N, -1)[:, -1], sh(kc), sh(ks), sh(vc), sh(vs), H, dh, Hkv)
+    kc2, ks2, _ = oracle.kv_quant(rep(khat))
+    vc2, vs2, _ = oracle.kv_quant(rep(vhat))
+    d2 = oracle.decode_attention(q.reshape(B, N, -1)[:, -1], sh(kc2), sh(ks2), sh(vc2), sh(vs2), H, dh)
+    assert np.array_equal(d1, d2)
+
+
+def _small_gqa_layer(seed):
+    shape = wl.Shape("g", d=256, H=4, F=160, layers=1, B=2, Nv=12, Nt=4, n_outlier=2, vis_begin=0)
+    Hkv, dh, d = 2, 64, 256
+    r = wl.rng(seed, "gqa-w")
+    mk = lambda n, k: oracle.quantize_weights((r.standard_normal((n, k)) * 0.02).astype(np.float32))
+    W = oracle.LayerWeights(qkv=mk(d + 2 * Hkv * dh, d), o=mk(d, d), gu=mk(2 * 160, d), down=mk(d, 160),
+                            gamma1=np.ones(d, np.float32), gamma2=np.ones(d, np.float32), eps=1e-5,
+                            H=4, dh=dh, F=160, Hkv=Hkv)
+    x = wl.hidden_state(shape, seed)
+    pos = wl.positions(shape)
+    cos, sin = wl.rope_tables(dh, shape.N + 1)
+    return shape, W, x, pos, cos, sin
+
+
+def test_gqa_layer_cache_width_and_decode_consistency():
+    shape, W, x, pos, cos, sin = _small_gqa_layer(6)
+    B, N, Nv, d = shape.B, shape.N, shape.Nv, 256
+    full = oracle.prefill_layer(W, x, pos, B, N, 0, Nv, Nv, cos, sin)
+    assert full["cache_kc"].shape == (B * N, 128) and full["cache_ks"].shape == (B * N, 2)     # K/V heads only
+    xb, pb = x.reshape(B, N, d), pos.reshape(B, N)
+    head = oracle.prefill_layer(W, xb[:, :N - 1].reshape(-1, d), pb[:, :N - 1].reshape(-1), B, N - 1, 0, Nv, Nv,
+                                cos, sin)
+    dec = oracle.decode_layer(W, xb[:, N - 1], pb[:, N - 1], oracle.cache_from_prefill(head, B), cos, sin)
+    last = np.arange(B) * N + N - 1
+    for key in ("q", "o", "x1", "x_next"):
+        assert np.array_equal(dec[key], full[key][last]), key
+    assert np.array_equal(dec["kc"], full["kc"][last])
