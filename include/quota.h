@@ -182,6 +182,16 @@ int quota_attention_prefill(const void *q_f16, const void *khat_f16,
                             float *cm_inter, float *cm_intra, void *ws,
                             void *stream);
 
+/* The same with grouped-query attention (the paper's second model family):
+ * q and o have H heads per row, khat / vhat have Hkv (rows of Hkv*dh), query
+ * head h reads K/V head h / (H/Hkv); the cues average over the H query heads.
+ * Requires H % Hkv == 0. */
+int quota_attention_prefill_gqa(const void *q_f16, const void *khat_f16,
+                                const void *vhat_f16, int B, int N, int H, int Hkv,
+                                int dh, int vis_begin, int Nv, void *o_f16,
+                                float *cm_inter, float *cm_intra, void *ws,
+                                void *stream);
+
 /* ---- scoring (Eq. 6-8) and budgeted top-k (Eq. 5, Eq. 9) ---------------- */
 
 typedef struct quota_score_params {
@@ -228,15 +238,20 @@ int quota_topk_prune(const float *score, int B, int Nv, int K,
 /* ---- the whole layer ---------------------------------------------------- */
 
 typedef struct quota_layer {
-    int H, dh, F;                /* d = H*dh                                  */
+    int H, dh, F;                /* d = H*dh (H query heads)                  */
     float eps;
     const float *gamma1, *gamma2; /* fp32 [d]                                 */
-    quota_weights qkv;           /* [3d][d], rows q | k | v                   */
+    quota_weights qkv;           /* [d + 2*Hkv*dh][d], rows q | k | v         */
     quota_weights o;             /* [d][d]                                    */
     quota_weights gu;            /* [2F][d], rows gate | up                   */
     quota_weights down;          /* [d][F]                                    */
     const float *cosT, *sinT;    /* fp32 [n_pos][dh/2]                        */
     int n_pos;
+    int Hkv;                     /* K/V heads (grouped-query attention: query
+                                  * head h reads K/V head h / (H/Hkv), the cues
+                                  * still average over the H query heads);
+                                  * 0 = H.  The layer's KV cache then has
+                                  * cache->H == Hkv.  Needs H % Hkv == 0.     */
 } quota_layer;
 
 /* Layer state (host struct, device buffers).  On entry x holds B sequences of
@@ -330,6 +345,12 @@ int quota_gflops_ratio(const int32_t *V_hat, int L, int V0, int T, int d, int F,
  * Requires dh == 64 or 128 and 1 <= len <= 8192 (QUOTA_ERR_SHAPE beyond). */
 int quota_attention_decode(const void *q_f16, const quota_kv_cache *cache,
                            void *o_f16, void *stream);
+
+/* The same for grouped-query attention: q and o have Hq heads per row, the
+ * cache holds cache->H K/V heads, query head h reads K/V head h / (Hq/cache->H).
+ * Requires Hq % cache->H == 0. */
+int quota_attention_decode_gqa(const void *q_f16, int Hq, const quota_kv_cache *cache,
+                               void *o_f16, void *stream);
 
 size_t quota_decode_workspace_bytes(const quota_layer *L, int B);
 

@@ -44,7 +44,7 @@ class Layer(C.Structure):
     _fields_ = [("H", C.c_int), ("dh", C.c_int), ("F", C.c_int), ("eps", C.c_float),
                 ("gamma1", C.c_void_p), ("gamma2", C.c_void_p),
                 ("qkv", Weights), ("o", Weights), ("gu", Weights), ("down", Weights),
-                ("cosT", C.c_void_p), ("sinT", C.c_void_p), ("n_pos", C.c_int)]
+                ("cosT", C.c_void_p), ("sinT", C.c_void_p), ("n_pos", C.c_int), ("Hkv", C.c_int)]
 
 
 class State(C.Structure):
@@ -169,6 +169,13 @@ def quota_kv_quant_append(k, v, B, N, H, dh, keep_rows, n_keep, cache: KVCache):
            "quota_kv_quant_append")
 
 
+def quota_attention_prefill_gqa(q, khat, vhat, B, N, H, Hkv, dh, vis_begin, Nv, o, cm_inter, cm_intra, ws):
+    _check(lib().quota_attention_prefill_gqa(_ptr(q, torch.float16), _ptr(khat, torch.float16),
+                                             _ptr(vhat, torch.float16), B, N, H, Hkv, dh, vis_begin, Nv,
+                                             _ptr(o), _ptr(cm_inter), _ptr(cm_intra), _ptr(ws), _stream()),
+           "quota_attention_prefill_gqa")
+
+
 def quota_attention_workspace_bytes(B, N, H, dh):
     return lib().quota_attention_workspace_bytes(B, N, H, dh)
 
@@ -248,6 +255,11 @@ def quota_gflops_ratio(V_hat, V0: int, T: int, d: int, F: int, F_vt: float = 0.0
 def quota_attention_decode(q, cache: KVCache, o):
     _check(lib().quota_attention_decode(_ptr(q, torch.float16), C.byref(cache), _ptr(o, torch.float16), _stream()),
            "quota_attention_decode")
+
+
+def quota_attention_decode_gqa(q, Hq, cache: KVCache, o):
+    _check(lib().quota_attention_decode_gqa(_ptr(q, torch.float16), int(Hq), C.byref(cache),
+                                            _ptr(o, torch.float16), _stream()), "quota_attention_decode_gqa")
 
 
 def quota_decode_workspace_bytes(L: Layer, B):

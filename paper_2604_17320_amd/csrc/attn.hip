@@ -28,7 +28,7 @@ struct AttnSmem {
 template <int DH>
 __global__ __launch_bounds__(256) void attn_fwd_kernel(
     const f16 *__restrict__ q, const f16 *__restrict__ khat, const f16 *__restrict__ vhat, int N,
-    int H, f16 *__restrict__ o, float *__restrict__ lse2, float scale_log2)
+    int H, int Hkv, f16 *__restrict__ o, float *__restrict__ lse2, float scale_log2)
 {
     constexpr int T = DH / 16;       // k-steps (16 channels each) of the QK product
     constexpr int DB = DH / 32;      // 32-channel blocks of the output
@@ -39,6 +39,9 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hl = lane >> 5;
     const int qw0 = q0 + wave * 32, qi = qw0 + l32;       // this lane's query
     const size_t base = (size_t)b * N * d + (size_t)h * DH;
+    // K/V rows have Hkv heads; query head h reads K/V head h / (H / Hkv)
+    const int dkv = Hkv * DH;
+    const size_t kvbase = (size_t)b * N * dkv + (size_t)(h / (H / Hkv)) * DH;
 
     f16x8 qf[T];
 #pragma unroll
@@ -69,9 +72,9 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
             rk[j].u = make_uint4(0, 0, 0, 0);
             rv[j].u = make_uint4(0, 0, 0, 0);
             if (kt0 + keyk < N)
-                rk[j].u = *reinterpret_cast<const uint4 *>(khat + base + (size_t)(kt0 + keyk) * d + 8 * ck);
+                rk[j].u = *reinterpret_cast<const uint4 *>(khat + kvbase + (size_t)(kt0 + keyk) * dkv + 8 * ck);
             if (kt0 + keyv < N)
-                rv[j].u = *reinterpret_cast<const uint4 *>(vhat + base + (size_t)(kt0 + keyv) * d + 8 * cv);
+                rv[j].u = *reinterpret_cast<const uint4 *>(vhat + kvbase + (size_t)(kt0 + keyv) * dkv + 8 * cv);
         }
     };
     fetch(0);
@@ -172,7 +175,7 @@ struct CmSmem {
 template <int DH>
 __global__ __launch_bounds__(256) void colmass_kernel(
     const f16 *__restrict__ q, const f16 *__restrict__ khat, const float *__restrict__ lse2, int N,
-    int H, int vis_begin, int Nv, float *__restrict__ partial, float scale_log2)
+    int H, int Hkv, int vis_begin, int Nv, float *__restrict__ partial, float scale_log2)
 {
     constexpr int T = DH / 16, CPR = DH / 8;
     __shared__ CmSmem<DH> sm;
@@ -188,7 +191,8 @@ __global__ __launch_bounds__(256) void colmass_kernel(
 #pragma unroll
     for (int t = 0; t < T; ++t) {
         if (key_ok)
-            kf[t] = *reinterpret_cast<const f16x8 *>(khat + base + (size_t)key * d + 16 * t + 8 * hl);
+            kf[t] = *reinterpret_cast<const f16x8 *>(khat + (size_t)b * N * (Hkv * DH) + (size_t)(h / (H / Hkv)) * DH +
+                                                     (size_t)key * (Hkv * DH) + 16 * t + 8 * hl);
         else
             kf[t] = f16x8{0, 0, 0, 0, 0, 0, 0, 0};
     }
@@ -280,13 +284,13 @@ extern "C" size_t quota_attention_workspace_bytes(int B, int N, int H, int dh)
 }
 
 int quota_internal_attention(const void *q_f16, const void *khat_f16, const void *vhat_f16, int B,
-                             int N, int H, int dh, int vis_begin, int Nv, void *o_f16,
+                             int N, int H, int Hkv, int dh, int vis_begin, int Nv, void *o_f16,
                              bool want_cues, void *ws, const float **partial_out, hipStream_t st)
 {
     if (!q_f16 || !khat_f16 || !vhat_f16 || !o_f16 || !ws) return QUOTA_ERR_NULL;
-    if (B <= 0 || N < 0 || H <= 0 || vis_begin < 0 || Nv < 0 || vis_begin + Nv > N)
+    if (B <= 0 || N < 0 || H <= 0 || Hkv <= 0 || vis_begin < 0 || Nv < 0 || vis_begin + Nv > N)
         return QUOTA_ERR_INVALID_ARG;
-    if (dh != 64 && dh != 128) return QUOTA_ERR_SHAPE;
+    if ((dh != 64 && dh != 128) || H % Hkv != 0) return QUOTA_ERR_SHAPE;
     if (partial_out) *partial_out = nullptr;
     if (N == 0) return QUOTA_OK;
     float *lse2 = (float *)ws;
@@ -296,24 +300,43 @@ int quota_internal_attention(const void *q_f16, const void *khat_f16, const void
     const f16 *q = (const f16 *)q_f16, *k = (const f16 *)khat_f16, *v = (const f16 *)vhat_f16;
     const double dM = (double)B * N, dd = (double)H * dh;
     {
-        ProfScope prof(QUOTA_K_ATTENTION_FWD, 4.0 * B * dd * ((double)N * (N + 1) / 2), 8.0 * dM * dd, st);
+        ProfScope prof(QUOTA_K_ATTENTION_FWD, 4.0 * B * dd * ((double)N * (N + 1) / 2),
+                       4.0 * dM * dd + 4.0 * dM * Hkv * dh, st);
         if (dh == 128)
-            attn_fwd_kernel<128><<<g1, blk, 0, st>>>(q, k, v, N, H, (f16 *)o_f16, lse2, scale_log2);
+            attn_fwd_kernel<128><<<g1, blk, 0, st>>>(q, k, v, N, H, Hkv, (f16 *)o_f16, lse2, scale_log2);
         else
-            attn_fwd_kernel<64><<<g1, blk, 0, st>>>(q, k, v, N, H, (f16 *)o_f16, lse2, scale_log2);
+            attn_fwd_kernel<64><<<g1, blk, 0, st>>>(q, k, v, N, H, Hkv, (f16 *)o_f16, lse2, scale_log2);
     }
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     if (Nv > 0 && want_cues) {
         dim3 g2((Nv + 127) / 128, H, B);
         // (query, visual key) pairs under the causal mask
         const double pairs = (double)Nv * (N - vis_begin) - (double)Nv * (Nv - 1) / 2;
-        ProfScope prof(QUOTA_K_ATTENTION_COLMASS, 2.0 * B * dd * pairs, 4.0 * dM * dd, st);
+        ProfScope prof(QUOTA_K_ATTENTION_COLMASS, 2.0 * B * dd * pairs, 2.0 * dM * dd + 2.0 * dM * Hkv * dh, st);
         if (dh == 128)
-            colmass_kernel<128><<<g2, blk, 0, st>>>(q, k, lse2, N, H, vis_begin, Nv, partial, scale_log2);
+            colmass_kernel<128><<<g2, blk, 0, st>>>(q, k, lse2, N, H, Hkv, vis_begin, Nv, partial, scale_log2);
         else
-            colmass_kernel<64><<<g2, blk, 0, st>>>(q, k, lse2, N, H, vis_begin, Nv, partial, scale_log2);
+            colmass_kernel<64><<<g2, blk, 0, st>>>(q, k, lse2, N, H, Hkv, vis_begin, Nv, partial, scale_log2);
         QUOTA_RETURN_IF_LAUNCH_FAILED();
         if (partial_out) *partial_out = partial;
+    }
+    return QUOTA_OK;
+}
+
+extern "C" int quota_attention_prefill_gqa(const void *q_f16, const void *khat_f16,
+                                           const void *vhat_f16, int B, int N, int H, int Hkv, int dh,
+                                           int vis_begin, int Nv, void *o_f16, float *cm_inter,
+                                           float *cm_intra, void *ws, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const float *partial = nullptr;
+    int rc = quota_internal_attention(q_f16, khat_f16, vhat_f16, B, N, H, Hkv, dh, vis_begin, Nv, o_f16,
+                                      cm_inter || cm_intra, ws, &partial, st);
+    if (rc != QUOTA_OK) return rc;
+    if (partial) {
+        colmass_reduce_kernel<<<dim3((B * Nv + 255) / 256), dim3(256), 0, st>>>(partial, B, H, Nv,
+                                                                                cm_inter, cm_intra);
+        QUOTA_RETURN_IF_LAUNCH_FAILED();
     }
     return QUOTA_OK;
 }
@@ -323,15 +346,6 @@ extern "C" int quota_attention_prefill(const void *q_f16, const void *khat_f16,
                                        int vis_begin, int Nv, void *o_f16, float *cm_inter,
                                        float *cm_intra, void *ws, void *stream)
 {
-    hipStream_t st = (hipStream_t)stream;
-    const float *partial = nullptr;
-    int rc = quota_internal_attention(q_f16, khat_f16, vhat_f16, B, N, H, dh, vis_begin, Nv, o_f16,
-                                      cm_inter || cm_intra, ws, &partial, st);
-    if (rc != QUOTA_OK) return rc;
-    if (partial) {
-        colmass_reduce_kernel<<<dim3((B * Nv + 255) / 256), dim3(256), 0, st>>>(partial, B, H, Nv,
-                                                                                cm_inter, cm_intra);
-        QUOTA_RETURN_IF_LAUNCH_FAILED();
-    }
-    return QUOTA_OK;
+    return quota_attention_prefill_gqa(q_f16, khat_f16, vhat_f16, B, N, H, H, dh, vis_begin, Nv, o_f16,
+                                       cm_inter, cm_intra, ws, stream);
 }

@@ -50,9 +50,9 @@ __global__ __launch_bounds__(256) void kv_append_rows_kernel(
 // through LDS in a fixed order.
 template <int DH>
 __global__ __launch_bounds__(256) void decode_attention_kernel(
-    const f16 *__restrict__ q, int d, const uint32_t *__restrict__ kc, const f16 *__restrict__ ks,
-    const uint32_t *__restrict__ vc, const f16 *__restrict__ vs, int capacity, int L,
-    f16 *__restrict__ o)
+    const f16 *__restrict__ q, int d, int dkv, int rep, const uint32_t *__restrict__ kc,
+    const f16 *__restrict__ ks, const uint32_t *__restrict__ vc, const f16 *__restrict__ vs, int capacity,
+    int L, f16 *__restrict__ o)
 {
     constexpr int WPT = DH / 8;             // packed dwords per token and head
     constexpr int GPT = DH / 64;            // scale groups per token and head
@@ -61,10 +61,11 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
     __shared__ float sc[DEC_LMAX];
     __shared__ float red[TL * DH];
     __shared__ float wred[8];
-    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-    const int n32 = d >> 3, ng = d >> 6;
+    const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int h = hq / rep;                 // K/V head read by query head hq (rep query heads per K/V head)
+    const int n32 = dkv >> 3, ng = dkv >> 6;
     if (tid < DH / 2) {
-        const f16 *qh = q + (size_t)b * d + h * DH + 8 * (tid >> 2) + (tid & 3);
+        const f16 *qh = q + (size_t)b * d + hq * DH + 8 * (tid >> 2) + (tid & 3);
         qp[tid] = h2{qh[0], qh[4]};
     }
     __syncthreads();
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
         float v = 0.0f;
 #pragma unroll 4
         for (int i = 0; i < TL; ++i) v += red[i * DH + tid];
-        o[(size_t)b * d + h * DH + tid] = (f16)(v * inv);
+        o[(size_t)b * d + hq * DH + tid] = (f16)(v * inv);
     }
 }
 
@@ -167,30 +168,38 @@ int quota_internal_kv_append_rows(int d, const uint8_t *skc, const void *sks, co
     return QUOTA_OK;
 }
 
-extern "C" int quota_attention_decode(const void *q_f16, const quota_kv_cache *cache, void *o_f16,
-                                      void *stream)
+extern "C" int quota_attention_decode_gqa(const void *q_f16, int Hq, const quota_kv_cache *cache,
+                                          void *o_f16, void *stream)
 {
     if (!q_f16 || !cache || !o_f16 || !cache->k_codes || !cache->k_scales || !cache->v_codes ||
         !cache->v_scales)
         return QUOTA_ERR_NULL;
-    if (cache->B <= 0 || cache->H <= 0 || cache->len <= 0 || cache->len > cache->capacity)
+    if (cache->B <= 0 || cache->H <= 0 || Hq <= 0 || cache->len <= 0 || cache->len > cache->capacity)
         return QUOTA_ERR_INVALID_ARG;
-    if ((cache->dh != 64 && cache->dh != 128) || cache->len > DEC_LMAX) return QUOTA_ERR_SHAPE;
-    const int d = cache->H * cache->dh;
+    if ((cache->dh != 64 && cache->dh != 128) || cache->len > DEC_LMAX || Hq % cache->H != 0)
+        return QUOTA_ERR_SHAPE;
+    const int d = Hq * cache->dh, dkv = cache->H * cache->dh, rep = Hq / cache->H;
     hipStream_t st = (hipStream_t)stream;
     const double rows = (double)cache->B * cache->len;
-    ProfScope prof(QUOTA_K_ATTENTION_DECODE, 4.0 * rows * d, rows * (d + d / 16.0) + 4.0 * cache->B * d, st);
-    dim3 grid(cache->H, cache->B), block(256);
+    ProfScope prof(QUOTA_K_ATTENTION_DECODE, 4.0 * rows * d, rows * (dkv + dkv / 16.0) + 4.0 * cache->B * d, st);
+    dim3 grid(Hq, cache->B), block(256);
     if (cache->dh == 128)
         decode_attention_kernel<128><<<grid, block, 0, st>>>(
-            (const f16 *)q_f16, d, (const uint32_t *)cache->k_codes, (const f16 *)cache->k_scales,
+            (const f16 *)q_f16, d, dkv, rep, (const uint32_t *)cache->k_codes, (const f16 *)cache->k_scales,
             (const uint32_t *)cache->v_codes, (const f16 *)cache->v_scales, cache->capacity,
             cache->len, (f16 *)o_f16);
     else
         decode_attention_kernel<64><<<grid, block, 0, st>>>(
-            (const f16 *)q_f16, d, (const uint32_t *)cache->k_codes, (const f16 *)cache->k_scales,
+            (const f16 *)q_f16, d, dkv, rep, (const uint32_t *)cache->k_codes, (const f16 *)cache->k_scales,
             (const uint32_t *)cache->v_codes, (const f16 *)cache->v_scales, cache->capacity,
             cache->len, (f16 *)o_f16);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
+}
+
+extern "C" int quota_attention_decode(const void *q_f16, const quota_kv_cache *cache, void *o_f16,
+                                      void *stream)
+{
+    if (!cache) return QUOTA_ERR_NULL;
+    return quota_attention_decode_gqa(q_f16, cache->H, cache, o_f16, stream);
 }

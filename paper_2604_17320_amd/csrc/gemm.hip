@@ -308,10 +308,12 @@ __global__ __launch_bounds__(256, WPE) void w4a4_gemm_kernel(
         // four waves; then every thread takes (row, 8-channel chunk) items and applies RoPE at
         // the token's position id (q and k tiles) and the 4-bit K/V group quantizer (k and v
         // tiles) exactly as the stand-alone kernel does.  q | k | v are column ranges
-        // [0,d) [d,2d) [2d,3d), so a tile lies in one of them.
+        // [0,d) [d,d+dkv) [d+dkv,d+2dkv), so a tile lies in one of them.
         f16 *tile = reinterpret_cast<f16 *>(lds_raw);
-        const int d = qe.d, region = n0 / d, c0 = n0 - region * d;     // tile-uniform
-        const int CPH = qe.dh >> 3, HALF = CPH >> 1, cpr = d >> 3, gpr = d >> 6;
+        const int d = qe.d, dkv = qe.dkv;
+        const int region = n0 < d ? 0 : (n0 < d + dkv ? 1 : 2);          // tile-uniform
+        const int c0 = n0 - (region == 0 ? 0 : (region == 1 ? d : d + dkv));
+        const int CPH = qe.dh >> 3, HALF = CPH >> 1, cpr = dkv >> 3, gpr = dkv >> 6;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             if (i) __syncthreads();                   // the previous row block has been read
@@ -363,7 +365,7 @@ __global__ __launch_bounds__(256, WPE) void w4a4_gemm_kernel(
                         f16 *xh = region == 1 ? qe.khat : qe.vhat;
                         uint32_t *codes = region == 1 ? qe.k_codes : qe.v_codes;
                         f16 *scales = region == 1 ? qe.k_scales : qe.v_scales;
-                        *reinterpret_cast<uint4 *>(xh + (size_t)m * d + col) = hat.u;
+                        *reinterpret_cast<uint4 *>(xh + (size_t)m * dkv + col) = hat.u;
                         const size_t orow = (size_t)m * qe.code_row_stride + qe.code_row_offset;
                         codes[orow * cpr + (col >> 3)] = word;
                         if ((c & 7) == 0) scales[orow * gpr + (col >> 6)] = sc;
@@ -591,16 +593,17 @@ int quota_internal_w4a4_gemm_qkv(const uint8_t *qa, const float *sa, int M, cons
         !qe->q_rot || !qe->khat || !qe->vhat || !qe->k_codes || !qe->k_scales || !qe->v_codes || !qe->v_scales)
         return QUOTA_ERR_NULL;
     if (M < 0 || qe->n_pos <= 0) return QUOTA_ERR_INVALID_ARG;
-    const int d = qe->d;
-    if ((qe->dh != 64 && qe->dh != 128) || d <= 0 || d % 128 != 0 || W->N != 3 * d || W->K % 32 != 0)
+    const int d = qe->d, dkv = qe->dkv;
+    if ((qe->dh != 64 && qe->dh != 128) || d <= 0 || d % 128 != 0 || dkv <= 0 || dkv % 128 != 0 ||
+        W->N != d + 2 * dkv || W->K % 32 != 0)
         return QUOTA_ERR_SHAPE;
     if (M == 0) return QUOTA_OK;
     f16 *y = (f16 *)y_opt;
     // (the 256-column tile is left out: with this epilogue it runs at its register limit)
     switch (choose_tile(M, W->N, W->K, false)) {
-    case 1: return launch<2, 1, 4, 2, true, false, true>(QUOTA_K_GEMM_64X128, qa, sa, M, W, y, 3 * d, nullptr, 0, nullptr, st, qe);
-    case 2: return launch<1, 1, 4, 2, true, false, true>(QUOTA_K_GEMM_32X128, qa, sa, M, W, y, 3 * d, nullptr, 0, nullptr, st, qe);
-    case 3: return launch<1, 1, 8, 4, true, false, true>(QUOTA_K_GEMM_32X128_DEEP, qa, sa, M, W, y, 3 * d, nullptr, 0, nullptr, st, qe);
-    default: return launch<2, 1, 3, 0, false, false, true, 3>(QUOTA_K_GEMM_64X128_LEAN, qa, sa, M, W, y, 3 * d, nullptr, 0, nullptr, st, qe);
+    case 1: return launch<2, 1, 4, 2, true, false, true>(QUOTA_K_GEMM_64X128, qa, sa, M, W, y, W->N, nullptr, 0, nullptr, st, qe);
+    case 2: return launch<1, 1, 4, 2, true, false, true>(QUOTA_K_GEMM_32X128, qa, sa, M, W, y, W->N, nullptr, 0, nullptr, st, qe);
+    case 3: return launch<1, 1, 8, 4, true, false, true>(QUOTA_K_GEMM_32X128_DEEP, qa, sa, M, W, y, W->N, nullptr, 0, nullptr, st, qe);
+    default: return launch<2, 1, 3, 0, false, false, true, 3>(QUOTA_K_GEMM_64X128_LEAN, qa, sa, M, W, y, W->N, nullptr, 0, nullptr, st, qe);
     }
 }

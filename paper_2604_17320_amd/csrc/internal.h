@@ -20,11 +20,11 @@ int quota_internal_score_topk(const float *sumsq, const float *ressq, long strid
 
 // attention + per-head column masses; partial_out (optional) [B][H][Nv][2] in the workspace
 int quota_internal_attention(const void *q_f16, const void *khat_f16, const void *vhat_f16, int B,
-                             int N, int H, int dh, int vis_begin, int Nv, void *o_f16,
+                             int N, int H, int Hkv, int dh, int vis_begin, int Nv, void *o_f16,
                              bool want_cues, void *ws, const float **partial_out, hipStream_t st);
 
 struct quota_compact_args {
-    int B, N, vis_begin, Nv, k_keep, n_keep, d;
+    int B, N, vis_begin, Nv, k_keep, n_keep, d, dkv;      // dkv: width of a K or V row (Hkv * dh)
     const int32_t *keep_idx;
     const void *x, *o;
     const int32_t *pos;
@@ -49,7 +49,7 @@ int quota_internal_kv_append_rows(int d, const uint8_t *skc, const void *sks, co
 struct quota_qkv_epilogue {
     const int32_t *pos;
     const float *cosT, *sinT;
-    int n_pos, d, dh;
+    int n_pos, d, dkv, dh;                  // q width H*dh, K/V width Hkv*dh
     f16 *q_rot, *khat, *vhat;
     uint32_t *k_codes, *v_codes;
     f16 *k_scales, *v_scales;
@@ -57,3 +57,9 @@ struct quota_qkv_epilogue {
 };
 int quota_internal_w4a4_gemm_qkv(const uint8_t *qa, const float *sa, int M, const quota_weights *W,
                                  void *y_opt, const quota_qkv_epilogue *qe, hipStream_t st);
+
+// quota_rope_kv_quant with Hkv K/V heads: qkv rows are q (H*dh) | k (Hkv*dh) | v (Hkv*dh).
+int quota_internal_rope_kv_quant(const void *qkv_f16, int M, int H, int Hkv, int dh, const int32_t *pos,
+                                 const float *cosT, const float *sinT, int n_pos, void *q_rot_f16,
+                                 void *khat_f16, void *vhat_f16, uint8_t *k_codes, void *k_scales,
+                                 uint8_t *v_codes, void *v_scales, hipStream_t st);

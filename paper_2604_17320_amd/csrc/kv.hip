@@ -9,62 +9,59 @@
 
 namespace {
 
-// thread t -> (row, 8-channel chunk c); q | k | v chunks at the same c
+// thread t -> (row, 8-channel chunk c of the q | k | v row).  q has d = H*dh channels, k and v
+// dkv = Hkv*dh each (dkv = d unless K/V heads are shared by groups of query heads).
 template <int DH>
 __global__ __launch_bounds__(256) void rope_kv_quant_kernel(
-    const f16 *__restrict__ qkv, int M, int d, const int32_t *__restrict__ pos, int n_pos,
+    const f16 *__restrict__ qkv, int M, int d, int dkv, const int32_t *__restrict__ pos, int n_pos,
     const float *__restrict__ cosT, const float *__restrict__ sinT, f16 *__restrict__ q_rot,
     f16 *__restrict__ khat, f16 *__restrict__ vhat, uint32_t *__restrict__ kc,
     f16 *__restrict__ ks, uint32_t *__restrict__ vc, f16 *__restrict__ vs)
 {
     constexpr int CPH = DH / 8, HALF = CPH / 2;     // chunks per head, per half head
-    const int cpr = d >> 3;                          // chunks per row
+    const int cq = d >> 3, ckv = dkv >> 3, cpr = cq + 2 * ckv;      // chunks: q part, k or v part, row
     long t = (long)blockIdx.x * 256 + threadIdx.x;
     if (t >= (long)M * cpr) return;
-    int row = (int)(t / cpr), c = (int)(t % cpr);
-    int cc = c % CPH;
-    bool second = cc >= HALF;
-    const f16 *base = qkv + (size_t)row * 3 * d + 8 * c;
-    Pack16 q, k, v;
-    q.u = *reinterpret_cast<const uint4 *>(base);
-    k.u = *reinterpret_cast<const uint4 *>(base + d);
-    v.u = *reinterpret_cast<const uint4 *>(base + 2 * d);
-    Pack16 qp, kp;                                   // rotate-half partner chunk
+    const int row = (int)(t / cpr), c = (int)(t % cpr);
+    // region boundaries are multiples of a head (16 or 8 chunks), so the 8 lanes of a KV group
+    // and the two halves of a head always sit in the same region
+    const int region = c < cq ? 0 : (c < cq + ckv ? 1 : 2);
+    const int cr = c - (region == 0 ? 0 : (region == 1 ? cq : cq + ckv));      // chunk inside the region
+    const int cc = cr % CPH;
+    const bool second = cc >= HALF;
+    Pack16 x, xp, xo;
+    x.u = *reinterpret_cast<const uint4 *>(qkv + (size_t)row * (d + 2 * dkv) + 8 * c);
+    if (region < 2) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        qp.w[i] = __shfl_xor(q.w[i], HALF, 64);
-        kp.w[i] = __shfl_xor(k.w[i], HALF, 64);
+        for (int i = 0; i < 4; ++i) xp.w[i] = __shfl_xor(x.w[i], HALF, 64);     // rotate-half partner chunk
+        const int pr = min(max(pos[row], 0), n_pos - 1);     // never index outside the tables
+        const float *cp = cosT + (size_t)pr * (DH / 2) + 8 * (cc % HALF);
+        const float *sp = sinT + (size_t)pr * (DH / 2) + 8 * (cc % HALF);
+        float cs[8], sn[8];
+        *reinterpret_cast<float4 *>(cs) = *reinterpret_cast<const float4 *>(cp);
+        *reinterpret_cast<float4 *>(cs + 4) = *reinterpret_cast<const float4 *>(cp + 4);
+        *reinterpret_cast<float4 *>(sn) = *reinterpret_cast<const float4 *>(sp);
+        *reinterpret_cast<float4 *>(sn + 4) = *reinterpret_cast<const float4 *>(sp + 4);
+        rope8(x, xp, cs, sn, second, xo);            // rotated q / k are fp16 tensors
+    } else {
+        xo = x;
     }
-    const int pr = min(max(pos[row], 0), n_pos - 1);     // never index outside the tables
-    const float *cp = cosT + (size_t)pr * (DH / 2) + 8 * (cc % HALF);
-    const float *sp = sinT + (size_t)pr * (DH / 2) + 8 * (cc % HALF);
-    float cs[8], sn[8];
-    *reinterpret_cast<float4 *>(cs) = *reinterpret_cast<const float4 *>(cp);
-    *reinterpret_cast<float4 *>(cs + 4) = *reinterpret_cast<const float4 *>(cp + 4);
-    *reinterpret_cast<float4 *>(sn) = *reinterpret_cast<const float4 *>(sp);
-    *reinterpret_cast<float4 *>(sn + 4) = *reinterpret_cast<const float4 *>(sp + 4);
-    Pack16 qo, ko;
-    float kf[8], vf[8];
-    rope8(q, qp, cs, sn, second, qo);
-    rope8(k, kp, cs, sn, second, ko);            // rotated k is an fp16 tensor
+    if (region == 0) {
+        *reinterpret_cast<uint4 *>(q_rot + (size_t)row * d + 8 * cr) = xo.u;
+        return;
+    }
+    float f[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        kf[e] = (float)ko.h[e];
-        vf[e] = (float)v.h[e];
-    }
-    *reinterpret_cast<uint4 *>(q_rot + (size_t)row * d + 8 * c) = qo.u;
-    Pack16 kh, vh;
-    f16 ksc, vsc;
-    uint32_t kw = kv_quant8(kf, &ksc, &kh);
-    uint32_t vw = kv_quant8(vf, &vsc, &vh);
-    *reinterpret_cast<uint4 *>(khat + (size_t)row * d + 8 * c) = kh.u;
-    *reinterpret_cast<uint4 *>(vhat + (size_t)row * d + 8 * c) = vh.u;
-    kc[(size_t)row * cpr + c] = kw;
-    vc[(size_t)row * cpr + c] = vw;
-    if ((c & 7) == 0) {
-        ks[(size_t)row * (cpr >> 3) + (c >> 3)] = ksc;
-        vs[(size_t)row * (cpr >> 3) + (c >> 3)] = vsc;
-    }
+    for (int e = 0; e < 8; ++e) f[e] = (float)xo.h[e];
+    Pack16 hat;
+    f16 sc;
+    const uint32_t word = kv_quant8(f, &sc, &hat);
+    f16 *xh = region == 1 ? khat : vhat;
+    uint32_t *codes = region == 1 ? kc : vc;
+    f16 *scales = region == 1 ? ks : vs;
+    *reinterpret_cast<uint4 *>(xh + (size_t)row * dkv + 8 * cr) = hat.u;
+    codes[(size_t)row * ckv + cr] = word;
+    if ((cr & 7) == 0) scales[(size_t)row * (ckv >> 3) + (cr >> 3)] = sc;
 }
 
 __global__ __launch_bounds__(256) void kv_quant_append_kernel(
@@ -104,7 +101,7 @@ __global__ __launch_bounds__(256) void kv_quant_append_kernel(
 // copied (o_out) and/or quantized for the output projection (oq_out, os_out).
 __global__ __launch_bounds__(256) void compact_rows_kernel(
     int N, int vis_begin, int Nv, int k_keep, int n_keep, const int32_t *__restrict__ keep_idx,
-    int d, const f16 *__restrict__ x, const f16 *__restrict__ o, const int32_t *__restrict__ pos,
+    int d, int dkv, const f16 *__restrict__ x, const f16 *__restrict__ o, const int32_t *__restrict__ pos,
     const uint32_t *__restrict__ skc, const f16 *__restrict__ sks, const uint32_t *__restrict__ svc,
     const f16 *__restrict__ svs, f16 *__restrict__ x_out, f16 *__restrict__ o_out,
     uint32_t *__restrict__ oq_out, float *__restrict__ os_out,
@@ -147,11 +144,12 @@ __global__ __launch_bounds__(256) void compact_rows_kernel(
         quantize_cached_row<false, ROW_THREADS, ROW_MAXCHUNK>(v, n16, threadIdx.x, a, oq_out + drow * n16, s);
         if (threadIdx.x == 0) os_out[drow] = s;
     }
-    for (int i = threadIdx.x; i < n16; i += 256) {          // d/8 dwords of codes per row
-        ckc[crow * n16 + i] = skc[srow * n16 + i];
-        cvc[crow * n16 + i] = svc[srow * n16 + i];
+    const int nkv = dkv >> 3;     // dwords of codes per K or V row
+    for (int i = threadIdx.x; i < nkv; i += 256) {
+        ckc[crow * nkv + i] = skc[srow * nkv + i];
+        cvc[crow * nkv + i] = svc[srow * nkv + i];
     }
-    const int ng = d >> 6;
+    const int ng = dkv >> 6;
     for (int i = threadIdx.x; i < ng; i += 256) {
         cks[crow * ng + i] = sks[srow * ng + i];
         cvs[crow * ng + i] = svs[srow * ng + i];
@@ -170,10 +168,10 @@ int quota_internal_compact(const quota_compact_args *a, hipStream_t st)
     if (c->len + a->n_keep > c->capacity) return QUOTA_ERR_CAPACITY;
     if (a->d % 8 != 0 || a->d > ROW_MAXCHUNK * ROW_THREADS * 8) return QUOTA_ERR_SHAPE;
     if (a->n_keep == 0) return QUOTA_OK;
-    const double rows = (double)a->n_keep * a->B, dd = a->d;
-    ProfScope prof(QUOTA_K_COMPACT_ROWS, 0, rows * (2 * (4 * dd + dd + dd / 16) + 8), st);
+    const double rows = (double)a->n_keep * a->B, dd = a->d, dk = a->dkv;
+    ProfScope prof(QUOTA_K_COMPACT_ROWS, 0, rows * (2 * (4 * dd + dk + dk / 16) + 8), st);
     compact_rows_kernel<<<dim3(a->n_keep, a->B), dim3(256), 0, st>>>(
-        a->N, a->vis_begin, a->Nv, a->k_keep, a->n_keep, a->keep_idx, a->d, (const f16 *)a->x,
+        a->N, a->vis_begin, a->Nv, a->k_keep, a->n_keep, a->keep_idx, a->d, a->dkv, (const f16 *)a->x,
         (const f16 *)a->o, a->pos, (const uint32_t *)a->skc, (const f16 *)a->sks,
         (const uint32_t *)a->svc, (const f16 *)a->svs, (f16 *)a->x_out, (f16 *)a->o_out, (uint32_t *)a->oq_out, a->os_out, a->pos_out,
         a->rows_out, c->capacity, c->len, (uint32_t *)c->k_codes, (f16 *)c->k_scales,
@@ -183,35 +181,44 @@ int quota_internal_compact(const quota_compact_args *a, hipStream_t st)
     return QUOTA_OK;
 }
 
+int quota_internal_rope_kv_quant(const void *qkv_f16, int M, int H, int Hkv, int dh, const int32_t *pos,
+                                 const float *cosT, const float *sinT, int n_pos, void *q_rot_f16,
+                                 void *khat_f16, void *vhat_f16, uint8_t *k_codes, void *k_scales,
+                                 uint8_t *v_codes, void *v_scales, hipStream_t st)
+{
+    if (!qkv_f16 || !pos || !cosT || !sinT || !q_rot_f16 || !khat_f16 || !vhat_f16 || !k_codes ||
+        !k_scales || !v_codes || !v_scales)
+        return QUOTA_ERR_NULL;
+    if (M < 0 || H <= 0 || Hkv <= 0 || n_pos <= 0) return QUOTA_ERR_INVALID_ARG;
+    if ((dh != 64 && dh != 128) || H % Hkv != 0) return QUOTA_ERR_SHAPE;
+    if (M == 0) return QUOTA_OK;
+    const int d = H * dh, dkv = Hkv * dh;
+    long total = (long)M * ((d + 2 * dkv) >> 3);
+    dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    ProfScope prof(QUOTA_K_ROPE_KV_QUANT, 0,
+                   (double)M * (2.0 * (d + 2 * dkv) + 2.0 * d + dkv * (4 + 1 + 1.0 / 16)) + 4.0 * M, st);
+    if (dh == 128)
+        rope_kv_quant_kernel<128><<<grid, block, 0, st>>>(
+            (const f16 *)qkv_f16, M, d, dkv, pos, n_pos, cosT, sinT, (f16 *)q_rot_f16, (f16 *)khat_f16,
+            (f16 *)vhat_f16, (uint32_t *)k_codes, (f16 *)k_scales, (uint32_t *)v_codes,
+            (f16 *)v_scales);
+    else
+        rope_kv_quant_kernel<64><<<grid, block, 0, st>>>(
+            (const f16 *)qkv_f16, M, d, dkv, pos, n_pos, cosT, sinT, (f16 *)q_rot_f16, (f16 *)khat_f16,
+            (f16 *)vhat_f16, (uint32_t *)k_codes, (f16 *)k_scales, (uint32_t *)v_codes,
+            (f16 *)v_scales);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    return QUOTA_OK;
+}
+
 extern "C" int quota_rope_kv_quant(const void *qkv_f16, int M, int H, int dh, const int32_t *pos,
                                    const float *cosT, const float *sinT, int n_pos,
                                    void *q_rot_f16, void *khat_f16, void *vhat_f16,
                                    uint8_t *k_codes, void *k_scales, uint8_t *v_codes,
                                    void *v_scales, void *stream)
 {
-    if (!qkv_f16 || !pos || !cosT || !sinT || !q_rot_f16 || !khat_f16 || !vhat_f16 || !k_codes ||
-        !k_scales || !v_codes || !v_scales)
-        return QUOTA_ERR_NULL;
-    if (M < 0 || H <= 0 || n_pos <= 0) return QUOTA_ERR_INVALID_ARG;
-    if (dh != 64 && dh != 128) return QUOTA_ERR_SHAPE;
-    if (M == 0) return QUOTA_OK;
-    int d = H * dh;
-    long total = (long)M * (d >> 3);
-    dim3 grid((unsigned)((total + 255) / 256)), block(256);
-    hipStream_t st = (hipStream_t)stream;
-    ProfScope prof(QUOTA_K_ROPE_KV_QUANT, 0, (double)M * d * (6 + 6 + 1 + 1.0 / 16) + 4.0 * M, st);
-    if (dh == 128)
-        rope_kv_quant_kernel<128><<<grid, block, 0, st>>>(
-            (const f16 *)qkv_f16, M, d, pos, n_pos, cosT, sinT, (f16 *)q_rot_f16, (f16 *)khat_f16,
-            (f16 *)vhat_f16, (uint32_t *)k_codes, (f16 *)k_scales, (uint32_t *)v_codes,
-            (f16 *)v_scales);
-    else
-        rope_kv_quant_kernel<64><<<grid, block, 0, st>>>(
-            (const f16 *)qkv_f16, M, d, pos, n_pos, cosT, sinT, (f16 *)q_rot_f16, (f16 *)khat_f16,
-            (f16 *)vhat_f16, (uint32_t *)k_codes, (f16 *)k_scales, (uint32_t *)v_codes,
-            (f16 *)v_scales);
-    QUOTA_RETURN_IF_LAUNCH_FAILED();
-    return QUOTA_OK;
+    return quota_internal_rope_kv_quant(qkv_f16, M, H, H, dh, pos, cosT, sinT, n_pos, q_rot_f16, khat_f16,
+                                        vhat_f16, k_codes, k_scales, v_codes, v_scales, (hipStream_t)stream);
 }
 
 extern "C" int quota_kv_quant_append(const void *k_f16, const void *v_f16, int B, int N, int H,

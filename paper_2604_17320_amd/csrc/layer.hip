@@ -7,6 +7,9 @@
 
 namespace {
 
+// K/V heads of a layer (0 in the descriptor means: as many as query heads)
+inline int kv_heads(const quota_layer *L) { return L->Hkv > 0 ? L->Hkv : L->H; }
+
 struct Carver {
     char *base;
     size_t off;
@@ -33,23 +36,23 @@ struct LayerWs {
     size_t bytes;
 };
 
-LayerWs carve(void *ws, int B, int N, int H, int dh, int F)
+LayerWs carve(void *ws, int B, int N, int H, int Hkv, int dh, int F)
 {
     Carver c{(char *)ws, 0};
     LayerWs w;
-    size_t M = (size_t)B * N, d = (size_t)H * dh;
+    size_t M = (size_t)B * N, d = (size_t)H * dh, dkv = (size_t)Hkv * dh;
     size_t kmax = d > (size_t)F ? d : (size_t)F;
     w.qa = c.take<uint8_t>(M * kmax / 2);
     w.sa = c.take<float>(M);
-    w.qkv = c.take<f16>(M * 3 * d);
+    w.qkv = c.take<f16>(M * (d + 2 * dkv));
     w.q_rot = c.take<f16>(M * d);
-    w.khat = c.take<f16>(M * d);
-    w.vhat = c.take<f16>(M * d);
+    w.khat = c.take<f16>(M * dkv);
+    w.vhat = c.take<f16>(M * dkv);
     w.o = c.take<f16>(M * d);
-    w.skc = c.take<uint8_t>(M * d / 2);
-    w.svc = c.take<uint8_t>(M * d / 2);
-    w.sks = c.take<f16>(M * d / 64);
-    w.svs = c.take<f16>(M * d / 64);
+    w.skc = c.take<uint8_t>(M * dkv / 2);
+    w.svc = c.take<uint8_t>(M * dkv / 2);
+    w.sks = c.take<f16>(M * dkv / 64);
+    w.svs = c.take<f16>(M * dkv / 64);
     w.sumsq = c.take<float>(M);
     w.ressq = c.take<float>(M);
     w.cm_inter = c.take<float>(M);
@@ -97,9 +100,10 @@ int dump(void *dst, const void *src, size_t bytes, hipStream_t st)
 static int qkv_rope_kv_quant(const quota_layer *L, const LayerWs &w, int M, const int32_t *pos,
                              bool want_qkv, hipStream_t st, quota_kv_cache *append_to = nullptr)
 {
-    const int d = L->H * L->dh;
+    const int d = L->H * L->dh, Hkv = kv_heads(L), dkv = Hkv * L->dh;
     quota_qkv_epilogue qe;
-    qe.pos = pos; qe.cosT = L->cosT; qe.sinT = L->sinT; qe.n_pos = L->n_pos; qe.d = d; qe.dh = L->dh;
+    qe.pos = pos; qe.cosT = L->cosT; qe.sinT = L->sinT; qe.n_pos = L->n_pos; qe.d = d; qe.dkv = dkv;
+    qe.dh = L->dh;
     qe.q_rot = w.q_rot; qe.khat = w.khat; qe.vhat = w.vhat;
     qe.k_codes = (uint32_t *)w.skc; qe.v_codes = (uint32_t *)w.svc;
     qe.k_scales = w.sks; qe.v_scales = w.svs;
@@ -114,16 +118,16 @@ static int qkv_rope_kv_quant(const quota_layer *L, const LayerWs &w, int M, cons
         if (rc == QUOTA_OK && append_to) append_to->len += 1;
         return rc;
     }
-    TRY(quota_w4a4_gemm(w.qa, w.sa, M, &L->qkv, w.qkv, 3 * d, nullptr, 0, nullptr, st));
-    TRY(quota_rope_kv_quant(w.qkv, M, L->H, L->dh, pos, L->cosT, L->sinT, L->n_pos, w.q_rot, w.khat,
-                            w.vhat, w.skc, w.sks, w.svc, w.svs, st));
-    return append_to ? quota_internal_kv_append_rows(d, w.skc, w.sks, w.svc, w.svs, append_to, st) : QUOTA_OK;
+    TRY(quota_w4a4_gemm(w.qa, w.sa, M, &L->qkv, w.qkv, d + 2 * dkv, nullptr, 0, nullptr, st));
+    TRY(quota_internal_rope_kv_quant(w.qkv, M, L->H, Hkv, L->dh, pos, L->cosT, L->sinT, L->n_pos, w.q_rot,
+                                     w.khat, w.vhat, w.skc, w.sks, w.svc, w.svs, st));
+    return append_to ? quota_internal_kv_append_rows(dkv, w.skc, w.sks, w.svc, w.svs, append_to, st) : QUOTA_OK;
 }
 
 extern "C" size_t quota_prefill_workspace_bytes(const quota_layer *L, int B, int N)
 {
     if (!L || B <= 0 || N <= 0 || L->H <= 0 || L->dh <= 0 || L->F <= 0) return 0;
-    return carve(nullptr, B, N, L->H, L->dh, L->F).bytes;
+    return carve(nullptr, B, N, L->H, kv_heads(L), L->dh, L->F).bytes;
 }
 
 extern "C" int quota_prefill_layer(const quota_layer *L, quota_state *s, int K_l,
@@ -135,18 +139,18 @@ extern "C" int quota_prefill_layer(const quota_layer *L, quota_state *s, int K_l
         return QUOTA_ERR_NULL;
     const int B = s->B, N = s->N, vb = s->vis_begin, Nv = s->Nv, H = L->H, dh = L->dh, F = L->F;
     if (B <= 0 || N <= 0 || vb < 0 || Nv < 0 || vb + Nv > N || K_l < 0) return QUOTA_ERR_INVALID_ARG;
-    const int d = H * dh;
-    if ((dh != 64 && dh != 128) || F % 32 != 0) return QUOTA_ERR_SHAPE;
-    if (L->qkv.N != 3 * d || L->qkv.K != d || L->o.N != d || L->o.K != d || L->gu.N != 2 * F ||
+    const int d = H * dh, Hkv = kv_heads(L), dkv = Hkv * dh;
+    if ((dh != 64 && dh != 128) || F % 32 != 0 || H % Hkv != 0) return QUOTA_ERR_SHAPE;
+    if (L->qkv.N != d + 2 * dkv || L->qkv.K != d || L->o.N != d || L->o.K != d || L->gu.N != 2 * F ||
         L->gu.K != d || L->down.N != d || L->down.K != F)
         return QUOTA_ERR_SHAPE;
-    if (cache->B != B || cache->H != H || cache->dh != dh) return QUOTA_ERR_SHAPE;
+    if (cache->B != B || cache->H != Hkv || cache->dh != dh) return QUOTA_ERR_SHAPE;
     const int k_keep = K_l < Nv ? K_l : Nv;
     const int n_keep = N - Nv + k_keep;
     if (cache->len + n_keep > cache->capacity) return QUOTA_ERR_CAPACITY;
 
     hipStream_t st = (hipStream_t)stream;
-    LayerWs w = carve(ws, B, N, H, dh, F);
+    LayerWs w = carve(ws, B, N, H, Hkv, dh, F);
     const int M = B * N, Mk = B * n_keep;
     static const quota_taps no_taps = {};
     const quota_taps *t = taps ? taps : &no_taps;
@@ -155,10 +159,10 @@ extern "C" int quota_prefill_layer(const quota_layer *L, quota_state *s, int K_l
     TRY(quota_rmsnorm_quantize_act(s->x, M, d, d, L->gamma1, L->eps, w.qa, w.sa, w.sumsq, w.ressq,
                                    nullptr, st));
     TRY(qkv_rope_kv_quant(L, w, M, s->pos, t->qkv != nullptr, st));
-    TRY(dump(t->qkv, w.qkv, (size_t)M * 3 * d * 2, st));
+    TRY(dump(t->qkv, w.qkv, (size_t)M * (d + 2 * dkv) * 2, st));
     TRY(dump(t->q_rot, w.q_rot, (size_t)M * d * 2, st));
     const float *partial = nullptr;     // per-head column masses; their head mean is taken by the score kernel
-    TRY(quota_internal_attention(w.q_rot, w.khat, w.vhat, B, N, H, dh, vb, Nv, w.o, true, w.attn_ws,
+    TRY(quota_internal_attention(w.q_rot, w.khat, w.vhat, B, N, H, Hkv, dh, vb, Nv, w.o, true, w.attn_ws,
                                  &partial, st));
     TRY(dump(t->o, w.o, (size_t)M * d * 2, st));
     const f16 *o_used = t->inject_o ? (const f16 *)t->inject_o : w.o;
@@ -197,7 +201,7 @@ extern "C" int quota_prefill_layer(const quota_layer *L, quota_state *s, int K_l
     // attention-output rows leave the gather already quantized for the output projection
     quota_compact_args ca;
     ca.B = B; ca.N = N; ca.vis_begin = vb; ca.Nv = Nv; ca.k_keep = k_keep; ca.n_keep = n_keep;
-    ca.d = d; ca.keep_idx = w.keep_idx; ca.x = s->x; ca.o = o_used; ca.pos = s->pos;
+    ca.d = d; ca.dkv = dkv; ca.keep_idx = w.keep_idx; ca.x = s->x; ca.o = o_used; ca.pos = s->pos;
     ca.skc = w.skc; ca.sks = w.sks; ca.svc = w.svc; ca.svs = w.svs;
     ca.x_out = w.x_keep; ca.o_out = nullptr; ca.oq_out = w.qa; ca.os_out = w.sa;
     ca.pos_out = s->pos_out; ca.rows_out = w.rows;
@@ -233,18 +237,18 @@ extern "C" int quota_decode_layer(const quota_layer *L, const void *x_f16, const
     if (!L || !x_f16 || !pos || !cache || !x_out_f16 || !ws || !L->gamma1 || !L->gamma2 || !L->cosT ||
         !L->sinT)
         return QUOTA_ERR_NULL;
-    const int H = L->H, dh = L->dh, F = L->F, d = H * dh;
+    const int H = L->H, dh = L->dh, F = L->F, d = H * dh, Hkv = kv_heads(L), dkv = Hkv * dh;
     if (B <= 0) return QUOTA_ERR_INVALID_ARG;
-    if ((dh != 64 && dh != 128) || F % 32 != 0) return QUOTA_ERR_SHAPE;
-    if (L->qkv.N != 3 * d || L->qkv.K != d || L->o.N != d || L->o.K != d || L->gu.N != 2 * F ||
+    if ((dh != 64 && dh != 128) || F % 32 != 0 || H % Hkv != 0) return QUOTA_ERR_SHAPE;
+    if (L->qkv.N != d + 2 * dkv || L->qkv.K != d || L->o.N != d || L->o.K != d || L->gu.N != 2 * F ||
         L->gu.K != d || L->down.N != d || L->down.K != F)
         return QUOTA_ERR_SHAPE;
-    if (cache->B != B || cache->H != H || cache->dh != dh) return QUOTA_ERR_SHAPE;
+    if (cache->B != B || cache->H != Hkv || cache->dh != dh) return QUOTA_ERR_SHAPE;
     if (cache->len < 0) return QUOTA_ERR_INVALID_ARG;
     if (cache->len + 1 > cache->capacity) return QUOTA_ERR_CAPACITY;
 
     hipStream_t st = (hipStream_t)stream;
-    LayerWs w = carve(ws, B, 1, H, dh, F);
+    LayerWs w = carve(ws, B, 1, H, Hkv, dh, F);
     static const quota_taps no_taps = {};
     const quota_taps *t = taps ? taps : &no_taps;
 
@@ -253,9 +257,9 @@ extern "C" int quota_decode_layer(const quota_layer *L, const void *x_f16, const
     // the new token's K/V join the cache first (written by the QKV epilogue itself, or by the
     // append kernel on the unfused path); attention then reads all of it in 4-bit form
     TRY(qkv_rope_kv_quant(L, w, B, pos, t->qkv != nullptr, st, cache));
-    TRY(dump(t->qkv, w.qkv, (size_t)B * 3 * d * 2, st));
+    TRY(dump(t->qkv, w.qkv, (size_t)B * (d + 2 * dkv) * 2, st));
     TRY(dump(t->q_rot, w.q_rot, (size_t)B * d * 2, st));
-    TRY(quota_attention_decode(w.q_rot, cache, w.o, st));
+    TRY(quota_attention_decode_gqa(w.q_rot, H, cache, w.o, st));
     TRY(dump(t->o, w.o, (size_t)B * d * 2, st));
     const f16 *o_used = t->inject_o ? (const f16 *)t->inject_o : w.o;
 

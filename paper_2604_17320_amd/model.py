@@ -77,12 +77,13 @@ class PrefillLayer:
 
     def __init__(self, H: int, dh: int, F: int, qkv: PackedLinear, o: PackedLinear, gu: PackedLinear,
                  down: PackedLinear, gamma1: torch.Tensor, gamma2: torch.Tensor, eps: float,
-                 cosT: torch.Tensor, sinT: torch.Tensor):
+                 cosT: torch.Tensor, sinT: torch.Tensor, Hkv: Optional[int] = None):
         self.H, self.dh, self.F, self.d = H, dh, F, H * dh
+        self.Hkv = H if Hkv is None else Hkv          # K/V heads (grouped-query attention)
         self.qkv, self.o, self.gu, self.down = qkv, o, gu, down
         self.gamma1, self.gamma2, self.cosT, self.sinT = gamma1, gamma2, cosT, sinT
         self.desc = qb.Layer(H, dh, F, eps, gamma1.data_ptr(), gamma2.data_ptr(), qkv.desc, o.desc,
-                             gu.desc, down.desc, cosT.data_ptr(), sinT.data_ptr(), cosT.shape[0])
+                             gu.desc, down.desc, cosT.data_ptr(), sinT.data_ptr(), cosT.shape[0], self.Hkv)
 
     def workspace_bytes(self, B: int, N: int) -> int:
         return qb.quota_prefill_workspace_bytes(self.desc, B, N)
@@ -130,7 +131,7 @@ class PrefillStack:
             n = n - nv + k
             nv = k
             self.n_keep.append(n)
-            self.caches.append(KVCache4(B, n + decode_capacity, L0.H, L0.dh))
+            self.caches.append(KVCache4(B, n + decode_capacity, L0.Hkv, L0.dh))
         self.dec_ws = None
         if decode_capacity:
             self.dec_ws = torch.empty(max(l.decode_workspace_bytes(B) for l in layers), dtype=torch.uint8,
