@@ -234,7 +234,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on ONE GPU (no sharding, no collectives); --gpus N>1 is not "
-              "supported. Batch parallelism would need no exchange step; see DESIGN.md.", file=sys.stderr)
+              "supported. Sequences are independent, so data parallelism over the batch would need no "
+              "exchange step.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
