@@ -226,8 +226,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--profile-steps", type=int, default=3)
-    ap.add_argument("--no-serving-shape", action="store_true",
-                    help="skip the supplementary per-kernel rates at the batch-16 serving shape")
+    ap.add_argument("--serving-shape", action="store_true",
+                    help="also report (outside the timed region) per-kernel rates at the batch-16 serving "
+                         "shape and the batch-16 prefill + decode steps on the same weights")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain elementwise copy of this many MiB (read + write), untimed: "
                          "the known-size kernel that HBM traffic counters are scaled by")
@@ -351,7 +352,7 @@ def main():
                              frac_int8_peak=round(gemm_ops / (gemm_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 4)
                              if gemm_ms else None, step_ms=round(gemm_ms / args.profile_steps, 4)),
                kernels=kern)
-    if not args.no_serving_shape:
+    if args.serving_shape:
         out["serving_shape_kernels"] = serving_shape_kernels(shape, args.seed)
         if args.config == "c3":
             out["serving_decode"] = serving_decode(shape, stack, budgets, args.seed)

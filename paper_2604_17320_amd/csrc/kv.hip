@@ -9,6 +9,65 @@
 
 namespace {
 
+// As many K/V heads as query heads: thread t -> (row, 8-channel chunk c) takes the q, k and v
+// chunk at the same c, three independent 16-byte loads in flight per thread.
+template <int DH>
+__global__ __launch_bounds__(256) void rope_kv_quant_mha_kernel(
+    const f16 *__restrict__ qkv, int M, int d, const int32_t *__restrict__ pos, int n_pos,
+    const float *__restrict__ cosT, const float *__restrict__ sinT, f16 *__restrict__ q_rot,
+    f16 *__restrict__ khat, f16 *__restrict__ vhat, uint32_t *__restrict__ kc,
+    f16 *__restrict__ ks, uint32_t *__restrict__ vc, f16 *__restrict__ vs)
+{
+    constexpr int CPH = DH / 8, HALF = CPH / 2;     // chunks per head, per half head
+    const int cpr = d >> 3;                          // chunks per row
+    long t = (long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= (long)M * cpr) return;
+    int row = (int)(t / cpr), c = (int)(t % cpr);
+    int cc = c % CPH;
+    bool second = cc >= HALF;
+    const f16 *base = qkv + (size_t)row * 3 * d + 8 * c;
+    Pack16 q, k, v;
+    q.u = *reinterpret_cast<const uint4 *>(base);
+    k.u = *reinterpret_cast<const uint4 *>(base + d);
+    v.u = *reinterpret_cast<const uint4 *>(base + 2 * d);
+    Pack16 qp, kp;                                   // rotate-half partner chunk
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        qp.w[i] = __shfl_xor(q.w[i], HALF, 64);
+        kp.w[i] = __shfl_xor(k.w[i], HALF, 64);
+    }
+    const int pr = min(max(pos[row], 0), n_pos - 1);     // never index outside the tables
+    const float *cp = cosT + (size_t)pr * (DH / 2) + 8 * (cc % HALF);
+    const float *sp = sinT + (size_t)pr * (DH / 2) + 8 * (cc % HALF);
+    float cs[8], sn[8];
+    *reinterpret_cast<float4 *>(cs) = *reinterpret_cast<const float4 *>(cp);
+    *reinterpret_cast<float4 *>(cs + 4) = *reinterpret_cast<const float4 *>(cp + 4);
+    *reinterpret_cast<float4 *>(sn) = *reinterpret_cast<const float4 *>(sp);
+    *reinterpret_cast<float4 *>(sn + 4) = *reinterpret_cast<const float4 *>(sp + 4);
+    Pack16 qo, ko;
+    float kf[8], vf[8];
+    rope8(q, qp, cs, sn, second, qo);
+    rope8(k, kp, cs, sn, second, ko);            // rotated k is an fp16 tensor
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        kf[e] = (float)ko.h[e];
+        vf[e] = (float)v.h[e];
+    }
+    *reinterpret_cast<uint4 *>(q_rot + (size_t)row * d + 8 * c) = qo.u;
+    Pack16 kh, vh;
+    f16 ksc, vsc;
+    uint32_t kw = kv_quant8(kf, &ksc, &kh);
+    uint32_t vw = kv_quant8(vf, &vsc, &vh);
+    *reinterpret_cast<uint4 *>(khat + (size_t)row * d + 8 * c) = kh.u;
+    *reinterpret_cast<uint4 *>(vhat + (size_t)row * d + 8 * c) = vh.u;
+    kc[(size_t)row * cpr + c] = kw;
+    vc[(size_t)row * cpr + c] = vw;
+    if ((c & 7) == 0) {
+        ks[(size_t)row * (cpr >> 3) + (c >> 3)] = ksc;
+        vs[(size_t)row * (cpr >> 3) + (c >> 3)] = vsc;
+    }
+}
+
 // thread t -> (row, 8-channel chunk c of the q | k | v row).  q has d = H*dh channels, k and v
 // dkv = Hkv*dh each (dkv = d unless K/V heads are shared by groups of query heads).
 template <int DH>
@@ -193,11 +252,20 @@ int quota_internal_rope_kv_quant(const void *qkv_f16, int M, int H, int Hkv, int
     if ((dh != 64 && dh != 128) || H % Hkv != 0) return QUOTA_ERR_SHAPE;
     if (M == 0) return QUOTA_OK;
     const int d = H * dh, dkv = Hkv * dh;
-    long total = (long)M * ((d + 2 * dkv) >> 3);
+    long total = Hkv == H ? (long)M * (d >> 3) : (long)M * ((d + 2 * dkv) >> 3);
     dim3 grid((unsigned)((total + 255) / 256)), block(256);
     ProfScope prof(QUOTA_K_ROPE_KV_QUANT, 0,
                    (double)M * (2.0 * (d + 2 * dkv) + 2.0 * d + dkv * (4 + 1 + 1.0 / 16)) + 4.0 * M, st);
-    if (dh == 128)
+    if (Hkv == H) {
+        if (dh == 128)
+            rope_kv_quant_mha_kernel<128><<<grid, block, 0, st>>>(
+                (const f16 *)qkv_f16, M, d, pos, n_pos, cosT, sinT, (f16 *)q_rot_f16, (f16 *)khat_f16,
+                (f16 *)vhat_f16, (uint32_t *)k_codes, (f16 *)k_scales, (uint32_t *)v_codes, (f16 *)v_scales);
+        else
+            rope_kv_quant_mha_kernel<64><<<grid, block, 0, st>>>(
+                (const f16 *)qkv_f16, M, d, pos, n_pos, cosT, sinT, (f16 *)q_rot_f16, (f16 *)khat_f16,
+                (f16 *)vhat_f16, (uint32_t *)k_codes, (f16 *)k_scales, (uint32_t *)v_codes, (f16 *)v_scales);
+    } else if (dh == 128)
         rope_kv_quant_kernel<128><<<grid, block, 0, st>>>(
             (const f16 *)qkv_f16, M, d, dkv, pos, n_pos, cosT, sinT, (f16 *)q_rot_f16, (f16 *)khat_f16,
             (f16 *)vhat_f16, (uint32_t *)k_codes, (f16 *)k_scales, (uint32_t *)v_codes,
