@@ -21,6 +21,7 @@
 // (high nibbles) int8 vectors; lane half h of k-step ks takes the even (ks
 // even) or odd (ks odd) vector of chunk 2*h + ks/2.
 #include "common.h"
+#include <cstdlib>
 #include "internal.h"
 #include "ropequant.h"
 
@@ -539,6 +540,12 @@ static int choose_tile(int M, int N, int K, bool allow_wide)
         {32, 128, 2, 4.0f, {0.27f, 0.46f, 0.0f}, 0.0f, 1.45f},      // <1,1,8,4> pipelined, deep prefetch
         {64, 128, 3, 6.0f, {0.53f, 0.75f, 1.06f}, 0.0f, 1.3f},      // <2,1,3,0>, three workgroups per CU
     };
+    // QUOTA_GEMM_TILE=0..4 in the environment pins the choice (tests cover every instantiation
+    // that way; also handy for tuning)
+    if (const char *e = getenv("QUOTA_GEMM_TILE")) {
+        const int v = atoi(e);
+        if (v >= (allow_wide ? 0 : 1) && v < 5) return v;
+    }
     const int G = (K + QUOTA_GROUP_W - 1) / QUOTA_GROUP_W;
     int best = -1;
     float best_t = 0.0f;

@@ -106,6 +106,7 @@ def assert_teacher_forced_exact(ref, got, shape, K):
 CASES = [
     # name, shape overrides, K
     ("c1", dict(), 19),
+    ("many_rows", dict(B=8, Nv=384, Nt=16), 100),      # 3200 rows: the tile choices of mid-sized launches
     ("c1_k20", dict(), 20),
     ("keep_all", dict(), 999),
     ("keep_none", dict(), 0),
@@ -239,3 +240,20 @@ def test_layer_without_taps_equals_layer_with_taps(qb):
     assert np.array_equal(host(pos_out), tapped["pos_next"][:n_keep])
     assert np.array_equal(unpack4(host(cache.k_codes)[0, :n_keep]), tapped["cache_kc"])
     assert np.array_equal(host(cache.v_scales)[0, :n_keep].view(np.uint16), tapped["cache_vs"].view(np.uint16))
+
+
+@pytest.mark.parametrize("tile", [1, 2, 3, 4])
+def test_layer_every_tile_with_fused_qkv_epilogue(qb, tile, monkeypatch):
+    """The QKV projection with its fused RoPE / KV-quantizer epilogue on each tile that carries it
+    (and every other GEMM of the layer on the same tile), teacher-forced bit-exact."""
+    monkeypatch.setenv("QUOTA_GEMM_TILE", str(tile))
+    base = wl.CONFIGS[0]
+    shape = wl.Shape("tile", d=base.d, H=base.H, F=base.F, layers=1, B=2, Nv=base.Nv, Nt=21,
+                     n_outlier=base.n_outlier, vis_begin=0)
+    W, L, cos, sin = build_layer(shape, 3, gamma_random=True)
+    x, pos = wl.hidden_state(shape, 3), wl.positions(shape)
+    K = 19
+    ref = oracle.prefill_layer(W, x, pos, shape.B, shape.N, 0, shape.Nv, K, cos, sin, prune_mid=True)
+    got = run_gpu(qb, L, shape, x, pos, K, dict(o=ref["o"], z=ref["z"], cm_inter=ref["cm_inter"],
+                                                cm_intra=ref["cm_intra"]))
+    assert_teacher_forced_exact(ref, got, shape, K)

@@ -198,6 +198,21 @@ def test_w4a4_gemm_bit_exact(qb, M, N, K):
     assert np.array_equal(host(y3).view(np.uint16), yr_ref.view(np.uint16))
 
 
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
+def test_w4a4_gemm_every_tile_bit_exact(qb, tile, monkeypatch):
+    """Each of the five tile instantiations, pinned through the environment, on shapes with ragged
+    rows, a ragged last group and several column tiles."""
+    from paper_2604_17320_amd.model import PackedLinear
+    monkeypatch.setenv("QUOTA_GEMM_TILE", str(tile))
+    for M, N, K in [(150, 1024, 1376), (70, 512, 4096)]:
+        qa, sa, qw, sw, res = _gemm_case(M, N, K, 23)
+        y_ref = oracle.w4a4_gemm(qa, sa, qw, sw, residual=res)
+        lin = PackedLinear.from_codes(dev(qw), dev(sw))
+        y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+        qb.quota_w4a4_gemm(dev(_pack4(qa)), dev(sa), M, lin.desc, y, N, dev(res), N)
+        assert np.array_equal(host(y).view(np.uint16), y_ref.view(np.uint16)), (tile, M, N, K)
+
+
 def test_w4a4_gemm_unit_scales_give_exact_integers(qb):
     from paper_2604_17320_amd.model import PackedLinear
     r = wl.rng(5, "unit")
