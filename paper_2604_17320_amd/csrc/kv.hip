@@ -158,6 +158,11 @@ __global__ __launch_bounds__(256) void kv_quant_append_kernel(
 // kept rows of the hidden state and the positions, moves their staged 4-bit
 // K/V rows into the layer's cache, and gathers the attention-output row --
 // copied (o_out) and/or quantized for the output projection (oq_out, os_out).
+// NCH = 16-byte chunks of a row per thread (2 covers 4096 columns, 8 covers 16384).  All loads
+// of a thread that do not depend on each other are issued together (unconditional, at clamped
+// indices): after the one dependent step -- the kept index, then the rows it names -- the kernel
+// needs a single memory round trip.
+template <int NCH>
 __global__ __launch_bounds__(256) void compact_rows_kernel(
     int N, int vis_begin, int Nv, int k_keep, int n_keep, const int32_t *__restrict__ keep_idx,
     int d, int dkv, const f16 *__restrict__ x, const f16 *__restrict__ o, const int32_t *__restrict__ pos,
@@ -168,54 +173,68 @@ __global__ __launch_bounds__(256) void compact_rows_kernel(
     uint32_t *__restrict__ ckc, f16 *__restrict__ cks, uint32_t *__restrict__ cvc,
     f16 *__restrict__ cvs)
 {
-    int j = blockIdx.x, b = blockIdx.y;
+    const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     int src;
     if (j < vis_begin) src = j;
     else if (j < vis_begin + k_keep) src = vis_begin + keep_idx[(size_t)b * k_keep + (j - vis_begin)];
     else src = j - k_keep + Nv;
     src = min(max(src, 0), N - 1);
-    size_t srow = (size_t)b * N + src, drow = (size_t)b * n_keep + j;
-    size_t crow = (size_t)b * capacity + len + j;
+    const size_t srow = (size_t)b * N + src, drow = (size_t)b * n_keep + j;
+    const size_t crow = (size_t)b * capacity + len + j;
     const int n16 = d >> 3;       // 16-byte pieces in an fp16 row
+    const int nkv = dkv >> 3;     // dwords of codes per K or V row (<= n16)
+    const int ng = dkv >> 6;      // group scales per K or V row
     const uint4 *xs = reinterpret_cast<const uint4 *>(x + srow * d);
     const uint4 *os = reinterpret_cast<const uint4 *>(o + srow * d);
-    uint4 *xd = reinterpret_cast<uint4 *>(x_out + drow * d);
-    // the attention-output row is cached: it is copied and/or fed to the activation quantizer
-    // in front of the output projection (same code path as the stand-alone quantizer)
+    const bool want_o = o_out || oq_out;
     __shared__ double sm[12];
-    Pack16 v[ROW_MAXCHUNK];
+    uint4 xv[NCH];
+    Pack16 v[NCH];
+    uint32_t kw[NCH], vw[NCH];
+#pragma unroll
+    for (int r = 0; r < NCH; ++r) {
+        const int i = tid + ROW_THREADS * r;
+        xv[r] = xs[min(i, n16 - 1)];
+        if (want_o) v[r].u = os[min(i, n16 - 1)];
+        kw[r] = skc[srow * nkv + min(i, nkv - 1)];
+        vw[r] = svc[srow * nkv + min(i, nkv - 1)];
+    }
+    const f16 ksv = sks[srow * ng + min(tid, ng - 1)], vsv = svs[srow * ng + min(tid, ng - 1)];
+    const int32_t pv = pos[srow];
+
+    // the attention-output row is copied and/or fed to the activation quantizer in front of the
+    // output projection (same code path as the stand-alone quantizer)
     float a = 0.0f;
 #pragma unroll
-    for (int r = 0; r < ROW_MAXCHUNK; ++r) {
-        int i = threadIdx.x + ROW_THREADS * r;
+    for (int r = 0; r < NCH; ++r) {
+        const int i = tid + ROW_THREADS * r;
         if (i < n16) {
-            xd[i] = xs[i];
-            v[r].u = os[i];
+            if (x_out) reinterpret_cast<uint4 *>(x_out + drow * d)[i] = xv[r];
             if (o_out) reinterpret_cast<uint4 *>(o_out + drow * d)[i] = v[r].u;
+            if (want_o) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf((float)v[r].h[e]));
+                for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf((float)v[r].h[e]));
+            }
         }
+        if (i < nkv) {
+            ckc[crow * nkv + i] = kw[r];
+            cvc[crow * nkv + i] = vw[r];
+        }
+    }
+    if (tid < ng) {
+        cks[crow * ng + tid] = ksv;
+        cvs[crow * ng + tid] = vsv;
+    }
+    if (tid == 0) {
+        pos_out[drow] = pv;
+        if (rows_out) rows_out[drow] = src;
     }
     if (oq_out) {
         double z0 = 0.0, z1 = 0.0;
         block_max_sum2<4>(a, z0, z1, sm);
         float s;
-        quantize_cached_row<false, ROW_THREADS, ROW_MAXCHUNK>(v, n16, threadIdx.x, a, oq_out + drow * n16, s);
-        if (threadIdx.x == 0) os_out[drow] = s;
-    }
-    const int nkv = dkv >> 3;     // dwords of codes per K or V row
-    for (int i = threadIdx.x; i < nkv; i += 256) {
-        ckc[crow * nkv + i] = skc[srow * nkv + i];
-        cvc[crow * nkv + i] = svc[srow * nkv + i];
-    }
-    const int ng = dkv >> 6;
-    for (int i = threadIdx.x; i < ng; i += 256) {
-        cks[crow * ng + i] = sks[srow * ng + i];
-        cvs[crow * ng + i] = svs[srow * ng + i];
-    }
-    if (threadIdx.x == 0) {
-        pos_out[drow] = pos[srow];
-        if (rows_out) rows_out[drow] = src;
+        quantize_cached_row<false, ROW_THREADS, NCH>(v, n16, tid, a, oq_out + drow * n16, s);
+        if (tid == 0) os_out[drow] = s;
     }
 }
 
@@ -225,11 +244,14 @@ int quota_internal_compact(const quota_compact_args *a, hipStream_t st)
 {
     quota_kv_cache *c = a->cache;
     if (c->len + a->n_keep > c->capacity) return QUOTA_ERR_CAPACITY;
-    if (a->d % 8 != 0 || a->d > ROW_MAXCHUNK * ROW_THREADS * 8) return QUOTA_ERR_SHAPE;
+    if (a->d % 8 != 0 || a->d > ROW_MAXCHUNK * ROW_THREADS * 8 || a->dkv > a->d || a->dkv < 64 ||
+        a->dkv / 64 > ROW_THREADS)
+        return QUOTA_ERR_SHAPE;
     if (a->n_keep == 0) return QUOTA_OK;
     const double rows = (double)a->n_keep * a->B, dd = a->d, dk = a->dkv;
     ProfScope prof(QUOTA_K_COMPACT_ROWS, 0, rows * (2 * (4 * dd + dk + dk / 16) + 8), st);
-    compact_rows_kernel<<<dim3(a->n_keep, a->B), dim3(256), 0, st>>>(
+    auto kernel = a->d <= 4096 ? compact_rows_kernel<2> : compact_rows_kernel<ROW_MAXCHUNK>;
+    kernel<<<dim3(a->n_keep, a->B), dim3(256), 0, st>>>(
         a->N, a->vis_begin, a->Nv, a->k_keep, a->n_keep, a->keep_idx, a->d, a->dkv, (const f16 *)a->x,
         (const f16 *)a->o, a->pos, (const uint32_t *)a->skc, (const f16 *)a->sks,
         (const uint32_t *)a->svc, (const f16 *)a->svs, (f16 *)a->x_out, (f16 *)a->o_out, (uint32_t *)a->oq_out, a->os_out, a->pos_out,

@@ -58,7 +58,9 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
 
 // ------------------------------------------------- activation quantizers
 
-// A row is owned by GROUP threads, each caching up to 8 chunks.  GROUP = 64 (rows of up to 4096
+// A row is owned by GROUP threads, each caching NCH chunks (2 or 8).  Every load of a thread is
+// issued before the first use (unconditional loads at clamped indices instead of guarded ones, so
+// that nothing separates them): one memory round trip per kernel.  GROUP = 64 (rows of up to 4096
 // columns): one WAVE per row, four rows per workgroup -- a lane issues all its 16-byte loads back
 // to back, the reductions are wave shuffles and there is no workgroup barrier.  GROUP = 256 (up to
 // 16384 columns): the whole workgroup owns the row and reduces through LDS.
@@ -74,13 +76,12 @@ __device__ __forceinline__ void group_reduce(float &mx, double &s0, double &s1, 
 }
 #define ROW_PROLOGUE()                                                                         \
     __shared__ double sm[12];                                                                  \
-    constexpr int NCH = ROW_MAXCHUNK;                                                          \
     const int lane = threadIdx.x % GROUP;                                                      \
     const int row = blockIdx.x * (ROW_THREADS / GROUP) + threadIdx.x / GROUP;                  \
     if (row >= M) return;     /* GROUP = 64: the whole wave leaves; GROUP = 256: never taken */ \
     (void)sm
 
-template <bool WANT_METRICS, int GROUP>
+template <bool WANT_METRICS, int GROUP, int NCH>
 __global__ __launch_bounds__(ROW_THREADS) void quantize_act_kernel(
     const f16 *__restrict__ x, int M, int d, long ldx, int rows_per_seq, long seq_stride,
     uint32_t *__restrict__ q, float *__restrict__ scale, float *__restrict__ sumsq,
@@ -94,10 +95,7 @@ __global__ __launch_bounds__(ROW_THREADS) void quantize_act_kernel(
     float a = 0.0f;
     double ss = 0.0;
 #pragma unroll
-    for (int r = 0; r < NCH; ++r) {
-        int c = lane + GROUP * r;
-        if (c < nchunk) v[r].u = xr[c];
-    }
+    for (int r = 0; r < NCH; ++r) v[r].u = xr[min(lane + GROUP * r, nchunk - 1)];
 #pragma unroll
     for (int r = 0; r < NCH; ++r) {
         int c = lane + GROUP * r;
@@ -125,7 +123,7 @@ __global__ __launch_bounds__(ROW_THREADS) void quantize_act_kernel(
     }
 }
 
-template <bool WANT_METRICS, int GROUP>
+template <bool WANT_METRICS, int GROUP, int NCH>
 __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
     const f16 *__restrict__ x, int M, int d, long ldx, const float *__restrict__ gamma, float eps,
     uint32_t *__restrict__ q, float *__restrict__ scale, float *__restrict__ sumsq,
@@ -137,10 +135,14 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
     Pack16 v[NCH];
     float a_raw = 0.0f;
     double ss = 0.0;
+    float4 ga[NCH][2];
 #pragma unroll
     for (int r = 0; r < NCH; ++r) {
-        int c = lane + GROUP * r;
-        if (c < nchunk) v[r].u = xr[c];
+        const int c = min(lane + GROUP * r, nchunk - 1);
+        v[r].u = xr[c];
+        const float4 *gp = reinterpret_cast<const float4 *>(gamma + 8 * c);
+        ga[r][0] = gp[0];
+        ga[r][1] = gp[1];
     }
 #pragma unroll
     for (int r = 0; r < NCH; ++r) {
@@ -165,8 +167,7 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
     for (int r = 0; r < NCH; ++r) {
         int c = lane + GROUP * r;
         if (c < nchunk) {
-            const float4 *gp = reinterpret_cast<const float4 *>(gamma + 8 * c);
-            float4 g0 = gp[0], g1 = gp[1];
+            const float4 g0 = ga[r][0], g1 = ga[r][1];
             float gm[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
     }
 }
 
-template <int GROUP>
+template <int GROUP, int NCH>
 __global__ __launch_bounds__(ROW_THREADS) void silu_mul_quantize_act_kernel(
     const f16 *__restrict__ gu, int M, int F, uint32_t *__restrict__ q, float *__restrict__ scale,
     f16 *__restrict__ z_out, const f16 *__restrict__ z_inject)
@@ -207,21 +208,28 @@ __global__ __launch_bounds__(ROW_THREADS) void silu_mul_quantize_act_kernel(
     const int nchunk = F >> 3;
     const uint4 *gr = reinterpret_cast<const uint4 *>(gu + (size_t)row * 2 * F);
     const uint4 *ur = reinterpret_cast<const uint4 *>(gu + (size_t)row * 2 * F + F);
-    Pack16 v[NCH];
+    Pack16 v[NCH], gg[NCH], uu[NCH];
     float a = 0.0f;
+    if (z_inject) {
+#pragma unroll
+        for (int r = 0; r < NCH; ++r)
+            v[r].u = reinterpret_cast<const uint4 *>(z_inject + (size_t)row * F)[min(lane + GROUP * r, nchunk - 1)];
+    } else {
+#pragma unroll
+        for (int r = 0; r < NCH; ++r) {
+            const int c = min(lane + GROUP * r, nchunk - 1);
+            gg[r].u = gr[c];
+            uu[r].u = ur[c];
+        }
+    }
 #pragma unroll
     for (int r = 0; r < NCH; ++r) {
         int c = lane + GROUP * r;
         if (c < nchunk) {
-            if (z_inject) {
-                v[r].u = reinterpret_cast<const uint4 *>(z_inject + (size_t)row * F)[c];
-            } else {
-                Pack16 g, u;
-                g.u = gr[c];
-                u.u = ur[c];
+            if (!z_inject) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    float gt = (float)g.h[e], up = (float)u.h[e];
+                    float gt = (float)gg[r].h[e], up = (float)uu[r].h[e];
                     // silu(g) = g / (1 + e^-g) with the hardware exp2 and reciprocal (a few fp32 ulp,
                     // far inside the fp16 rounding that follows)
                     float sg = gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt));
@@ -305,10 +313,17 @@ extern "C" int quota_quantize_act(const void *x_f16, int M, int d, int ldx, uint
     const dim3 grid(small ? (M + 3) / 4 : M), blk(ROW_THREADS);
     const f16 *x = (const f16 *)x_f16;
     uint32_t *q = (uint32_t *)q_packed;
-    if (metrics && small) quantize_act_kernel<true, 64><<<grid, blk, 0, st>>>(x, M, d, ldx, M, 0, q, scale, sumsq_opt, ressq_opt);
-    else if (metrics) quantize_act_kernel<true, 256><<<grid, blk, 0, st>>>(x, M, d, ldx, M, 0, q, scale, sumsq_opt, ressq_opt);
-    else if (small) quantize_act_kernel<false, 64><<<grid, blk, 0, st>>>(x, M, d, ldx, M, 0, q, scale, nullptr, nullptr);
-    else quantize_act_kernel<false, 256><<<grid, blk, 0, st>>>(x, M, d, ldx, M, 0, q, scale, nullptr, nullptr);
+    const bool few = (d >> 3) <= 2 * (small ? 64 : 256);      // two chunks per thread are enough
+#define QUOTA_LAUNCH_Q(MET, GRP, NCH) \
+    quantize_act_kernel<MET, GRP, NCH><<<grid, blk, 0, st>>>(x, M, d, ldx, M, 0, q, scale, sumsq_opt, ressq_opt)
+    if (metrics) {
+        if (small) { if (few) QUOTA_LAUNCH_Q(true, 64, 2); else QUOTA_LAUNCH_Q(true, 64, 8); }
+        else { if (few) QUOTA_LAUNCH_Q(true, 256, 2); else QUOTA_LAUNCH_Q(true, 256, 8); }
+    } else {
+        if (small) { if (few) QUOTA_LAUNCH_Q(false, 64, 2); else QUOTA_LAUNCH_Q(false, 64, 8); }
+        else { if (few) QUOTA_LAUNCH_Q(false, 256, 2); else QUOTA_LAUNCH_Q(false, 256, 8); }
+    }
+#undef QUOTA_LAUNCH_Q
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
 }
@@ -330,10 +345,18 @@ extern "C" int quota_rmsnorm_quantize_act(const void *x_f16, int M, int d, int l
     const f16 *x = (const f16 *)x_f16;
     uint32_t *q = (uint32_t *)q_packed;
     f16 *h = (f16 *)h_opt;
-    if (metrics && small) rmsnorm_quantize_act_kernel<true, 64><<<grid, blk, 0, st>>>(x, M, d, ldx, gamma, eps, q, scale, sumsq_opt, ressq_opt, h);
-    else if (metrics) rmsnorm_quantize_act_kernel<true, 256><<<grid, blk, 0, st>>>(x, M, d, ldx, gamma, eps, q, scale, sumsq_opt, ressq_opt, h);
-    else if (small) rmsnorm_quantize_act_kernel<false, 64><<<grid, blk, 0, st>>>(x, M, d, ldx, gamma, eps, q, scale, nullptr, nullptr, h);
-    else rmsnorm_quantize_act_kernel<false, 256><<<grid, blk, 0, st>>>(x, M, d, ldx, gamma, eps, q, scale, nullptr, nullptr, h);
+    const bool few = (d >> 3) <= 2 * (small ? 64 : 256);      // two chunks per thread are enough
+#define QUOTA_LAUNCH_R(MET, GRP, NCH)                                                                  \
+    rmsnorm_quantize_act_kernel<MET, GRP, NCH><<<grid, blk, 0, st>>>(x, M, d, ldx, gamma, eps, q, scale, \
+                                                                     sumsq_opt, ressq_opt, h)
+    if (metrics) {
+        if (small) { if (few) QUOTA_LAUNCH_R(true, 64, 2); else QUOTA_LAUNCH_R(true, 64, 8); }
+        else { if (few) QUOTA_LAUNCH_R(true, 256, 2); else QUOTA_LAUNCH_R(true, 256, 8); }
+    } else {
+        if (small) { if (few) QUOTA_LAUNCH_R(false, 64, 2); else QUOTA_LAUNCH_R(false, 64, 8); }
+        else { if (few) QUOTA_LAUNCH_R(false, 256, 2); else QUOTA_LAUNCH_R(false, 256, 8); }
+    }
+#undef QUOTA_LAUNCH_R
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
 }
@@ -348,12 +371,13 @@ extern "C" int quota_silu_mul_quantize_act(const void *gu_f16, int M, int F, uin
     ProfScope prof(QUOTA_K_SILU_MUL_QUANTIZE_ACT, 0, 4.5 * M * F + 4.0 * M, (hipStream_t)stream);
     const bool small = F <= 4096 && M >= ROW_WAVE_MIN_ROWS;
     const dim3 grid(small ? (M + 3) / 4 : M), blk(ROW_THREADS);
-    if (small)
-        silu_mul_quantize_act_kernel<64><<<grid, blk, 0, (hipStream_t)stream>>>(
-            (const f16 *)gu_f16, M, F, (uint32_t *)q_packed, scale, (f16 *)z_opt, (const f16 *)z_inject_opt);
-    else
-        silu_mul_quantize_act_kernel<256><<<grid, blk, 0, (hipStream_t)stream>>>(
-            (const f16 *)gu_f16, M, F, (uint32_t *)q_packed, scale, (f16 *)z_opt, (const f16 *)z_inject_opt);
+    const bool few = (F >> 3) <= 2 * (small ? 64 : 256);
+#define QUOTA_LAUNCH_S(GRP, NCH)                                                                      \
+    silu_mul_quantize_act_kernel<GRP, NCH><<<grid, blk, 0, (hipStream_t)stream>>>(                    \
+        (const f16 *)gu_f16, M, F, (uint32_t *)q_packed, scale, (f16 *)z_opt, (const f16 *)z_inject_opt)
+    if (small) { if (few) QUOTA_LAUNCH_S(64, 2); else QUOTA_LAUNCH_S(64, 8); }
+    else { if (few) QUOTA_LAUNCH_S(256, 2); else QUOTA_LAUNCH_S(256, 8); }
+#undef QUOTA_LAUNCH_S
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
 }
@@ -371,12 +395,13 @@ int quota_internal_vector_metrics(const void *v_f16, int B, int Nv, int d, int l
     ProfScope prof(QUOTA_K_QUANTIZE_ACT, 0, 2.0 * B * Nv * d + 8.0 * B * Nv, st);
     const bool small = d <= 4096 && B * Nv >= ROW_WAVE_MIN_ROWS;
     const dim3 grid(small ? (B * Nv + 3) / 4 : B * Nv), blk(ROW_THREADS);
-    if (small)
-        quantize_act_kernel<true, 64><<<grid, blk, 0, st>>>((const f16 *)v_f16, B * Nv, d, ldv, Nv, stride_b,
-                                                           nullptr, nullptr, sumsq, ressq);
-    else
-        quantize_act_kernel<true, 256><<<grid, blk, 0, st>>>((const f16 *)v_f16, B * Nv, d, ldv, Nv, stride_b,
-                                                            nullptr, nullptr, sumsq, ressq);
+    const bool few = (d >> 3) <= 2 * (small ? 64 : 256);
+#define QUOTA_LAUNCH_V(GRP, NCH)                                                                           \
+    quantize_act_kernel<true, GRP, NCH><<<grid, blk, 0, st>>>((const f16 *)v_f16, B * Nv, d, ldv, Nv, stride_b, \
+                                                              nullptr, nullptr, sumsq, ressq)
+    if (small) { if (few) QUOTA_LAUNCH_V(64, 2); else QUOTA_LAUNCH_V(64, 8); }
+    else { if (few) QUOTA_LAUNCH_V(256, 2); else QUOTA_LAUNCH_V(256, 8); }
+#undef QUOTA_LAUNCH_V
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
 }
