@@ -199,7 +199,9 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
     }
 }
 
-template <int GROUP, int NCH>
+// EARLY: every load before the first use (short launches, latency counts); otherwise chunk by
+// chunk (long launches: fewer live registers, more waves per SIMD to hide the latency instead).
+template <int GROUP, int NCH, bool EARLY>
 __global__ __launch_bounds__(ROW_THREADS) void silu_mul_quantize_act_kernel(
     const f16 *__restrict__ gu, int M, int F, uint32_t *__restrict__ q, float *__restrict__ scale,
     f16 *__restrict__ z_out, const f16 *__restrict__ z_inject)
@@ -214,7 +216,7 @@ __global__ __launch_bounds__(ROW_THREADS) void silu_mul_quantize_act_kernel(
 #pragma unroll
         for (int r = 0; r < NCH; ++r)
             v[r].u = reinterpret_cast<const uint4 *>(z_inject + (size_t)row * F)[min(lane + GROUP * r, nchunk - 1)];
-    } else {
+    } else if (EARLY) {
 #pragma unroll
         for (int r = 0; r < NCH; ++r) {
             const int c = min(lane + GROUP * r, nchunk - 1);
@@ -227,6 +229,7 @@ __global__ __launch_bounds__(ROW_THREADS) void silu_mul_quantize_act_kernel(
         int c = lane + GROUP * r;
         if (c < nchunk) {
             if (!z_inject) {
+                if (!EARLY) { gg[r].u = gr[c]; uu[r].u = ur[c]; }
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     float gt = (float)gg[r].h[e], up = (float)uu[r].h[e];
@@ -372,11 +375,16 @@ extern "C" int quota_silu_mul_quantize_act(const void *gu_f16, int M, int F, uin
     const bool small = F <= 4096 && M >= ROW_WAVE_MIN_ROWS;
     const dim3 grid(small ? (M + 3) / 4 : M), blk(ROW_THREADS);
     const bool few = (F >> 3) <= 2 * (small ? 64 : 256);
-#define QUOTA_LAUNCH_S(GRP, NCH)                                                                      \
-    silu_mul_quantize_act_kernel<GRP, NCH><<<grid, blk, 0, (hipStream_t)stream>>>(                    \
+#define QUOTA_LAUNCH_S(GRP, NCH, EARLY)                                                               \
+    silu_mul_quantize_act_kernel<GRP, NCH, EARLY><<<grid, blk, 0, (hipStream_t)stream>>>(             \
         (const f16 *)gu_f16, M, F, (uint32_t *)q_packed, scale, (f16 *)z_opt, (const f16 *)z_inject_opt)
-    if (small) { if (few) QUOTA_LAUNCH_S(64, 2); else QUOTA_LAUNCH_S(64, 8); }
-    else { if (few) QUOTA_LAUNCH_S(256, 2); else QUOTA_LAUNCH_S(256, 8); }
+    if (M >= ROW_WAVE_MIN_ROWS) {
+        if (small) { if (few) QUOTA_LAUNCH_S(64, 2, false); else QUOTA_LAUNCH_S(64, 8, false); }
+        else { if (few) QUOTA_LAUNCH_S(256, 2, false); else QUOTA_LAUNCH_S(256, 8, false); }
+    } else {
+        if (small) { if (few) QUOTA_LAUNCH_S(64, 2, true); else QUOTA_LAUNCH_S(64, 8, true); }
+        else { if (few) QUOTA_LAUNCH_S(256, 2, true); else QUOTA_LAUNCH_S(256, 8, true); }
+    }
 #undef QUOTA_LAUNCH_S
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
