@@ -323,7 +323,9 @@ def main():
                       avg_launch_us_net=round(max(ds["total_ms"] * 1e3 / ds["launches"] - bracket_ms * 1e3, 0.0), 2),
                       event_bracket_us=round(bracket_ms * 1e3, 2), empty_kernel_us=round(empty_kernel_ms * 1e3, 2),
                       launches_per_step=ds["launches"] // args.profile_steps)
-    traffic = measured_traffic(dom)
+    traffic_detail = measured_traffic(dom)
+    traffic = traffic_detail["bytes_per_launch"] if traffic_detail else None     # HBM bytes per launch
+    per_launch["traffic_detail"] = traffic_detail
     if ds["ops"] and dom.startswith("w4a4_gemm"):
         achieved = ds["ops"] / (ds["total_ms"] * 1e-3) / 1e12
         roofline = dict(kernel=dom, bound="mfma", achieved=round(achieved, 1), peak=PEAK_INT8_TOPS,
