@@ -19,6 +19,10 @@ namespace {
 
 constexpr int KT = 64;       // keys per tile (pass 1), queries per tile (pass 2)
 
+// 2^x on the transcendental unit, without the range handling of exp2f (its extra instructions only
+// matter for results below the smallest normal number, which are zero for a softmax anyway)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 template <int DH>
 struct AttnSmem {
     alignas(16) f16 k[KT][DH + 8];       // row stride = odd number of 16-byte units: conflict-free 16-byte reads
@@ -105,19 +109,31 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
             }
         }
         float mx = -INFINITY;
+        // only a tile that reaches this wave's diagonal or the end of the sequence needs the mask
+        if (kt0 + KT - 1 > qw0 || kt0 + KT > N) {
 #pragma unroll
-        for (int sb = 0; sb < 2; ++sb)
+            for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int key = kt0 + 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
-                float v = s[sb][r] * scale_log2;
-                v = (key <= qi && key < N) ? v : -INFINITY;
-                s[sb][r] = v;
-                mx = fmaxf(mx, v);
-            }
+                for (int r = 0; r < 16; ++r) {
+                    int key = kt0 + 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
+                    float v = s[sb][r] * scale_log2;
+                    v = (key <= qi && key < N) ? v : -INFINITY;
+                    s[sb][r] = v;
+                    mx = fmaxf(mx, v);
+                }
+        } else {
+#pragma unroll
+            for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float v = s[sb][r] * scale_log2;
+                    s[sb][r] = v;
+                    mx = fmaxf(mx, v);
+                }
+        }
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         float m_new = fmaxf(m_run, mx);
-        float alpha = exp2f(m_run - m_new);
+        float alpha = fast_exp2(m_run - m_new);
         m_run = m_new;
         float psum = 0.0f;
         // k-slot j of step u holds key 32 sb + 16 u + 8 (j / 4) + 4 hl + j % 4: registers 8u .. 8u+7
@@ -128,7 +144,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
             for (int u = 0; u < 2; ++u) {
                 float p[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) p[j] = exp2f(s[sb][8 * u + j] - m_new);
+                for (int j = 0; j < 8; ++j) p[j] = fast_exp2(s[sb][8 * u + j] - m_new);
                 psum += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
                 pf[sb][u] = f16x8{(f16)p[0], (f16)p[1], (f16)p[2], (f16)p[3],
                                   (f16)p[4], (f16)p[5], (f16)p[6], (f16)p[7]};
@@ -237,7 +253,7 @@ __global__ __launch_bounds__(256) void colmass_kernel(
             for (int r = 0; r < 16; ++r) {
                 int ql = 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
                 int qi = qt0 + ql;
-                float p = exp2f(s[r] * scale_log2 - sm.lse[ql]);
+                float p = fast_exp2(s[r] * scale_log2 - sm.lse[ql]);
                 p = (key_ok && key <= qi && qi < N) ? p : 0.0f;
                 bool vis = qi >= vis_begin && qi < vis_begin + Nv;
                 acc_vis += vis ? p : 0.0f;
