@@ -249,15 +249,31 @@ __global__ __launch_bounds__(256) void colmass_kernel(
                 f16x8 qf = *reinterpret_cast<const f16x8 *>(&sm.q[32 * sb + l32][16 * t + 8 * hl]);
                 s = __builtin_amdgcn_mfma_f32_32x32x16_f16(qf, kf[t], s, 0, 0, 0);
             }
+            // the causal / end-of-sequence mask is only needed when the query block reaches this
+            // wave's keys or the end of the sequence (lanes without a key accumulate values that
+            // are never stored)
+            const int qb0 = qt0 + 32 * sb;
+            if (qb0 < kwg + wave * 32 + 31 || qb0 + 32 > N) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int ql = 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
-                int qi = qt0 + ql;
-                float p = fast_exp2(s[r] * scale_log2 - sm.lse[ql]);
-                p = (key_ok && key <= qi && qi < N) ? p : 0.0f;
-                bool vis = qi >= vis_begin && qi < vis_begin + Nv;
-                acc_vis += vis ? p : 0.0f;
-                acc_txt += vis ? 0.0f : p;
+                for (int r = 0; r < 16; ++r) {
+                    int ql = 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
+                    int qi = qt0 + ql;
+                    float p = fast_exp2(s[r] * scale_log2 - sm.lse[ql]);
+                    p = (key <= qi && qi < N) ? p : 0.0f;
+                    bool vis = qi >= vis_begin && qi < vis_begin + Nv;
+                    acc_vis += vis ? p : 0.0f;
+                    acc_txt += vis ? 0.0f : p;
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    int ql = 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
+                    int qi = qt0 + ql;
+                    float p = fast_exp2(s[r] * scale_log2 - sm.lse[ql]);
+                    bool vis = qi >= vis_begin && qi < vis_begin + Nv;
+                    acc_vis += vis ? p : 0.0f;
+                    acc_txt += vis ? 0.0f : p;
+                }
             }
         }
     }
