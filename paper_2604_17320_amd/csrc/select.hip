@@ -25,6 +25,20 @@ __device__ __forceinline__ float key_float(uint32_t k)
     return __uint_as_float(u);
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave with DPP moves (no LDS crossbar): shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes, then lane 15 of rows 0 and 2 is added to rows 1 and 3,
+// then lane 31 to rows 2 and 3.  Lanes without a source add 0.
+__device__ __forceinline__ int wave_incl_scan(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);     // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);     // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);     // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);     // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);     // row_bcast:15 -> rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);     // row_bcast:31 -> rows 2, 3
+    return v;
+}
+
 // Exact k-th smallest (0-based rank) of the n keys key_at(i), computed by the
 // calling wave alone.  hist: 256 ints of LDS private to the wave.  All lanes
 // return the key.
@@ -44,12 +58,7 @@ __device__ uint32_t wave_radix_select(KeyAt key_at, int n, int rank, volatile in
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         int c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
-        int s = c0 + c1 + c2 + c3, incl = s;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            int t = __shfl_up(incl, off, 64);
-            if (lane >= off) incl += t;
-        }
+        const int s = c0 + c1 + c2 + c3, incl = wave_incl_scan(s);
         int excl = incl - s;
         bool mine = remaining >= excl && remaining < incl;      // exactly one lane
         int r = remaining - excl, digit = 4 * lane;
@@ -191,13 +200,7 @@ __device__ void score_phase(const MetricSrc &src, int B, int Nv, int b, const qu
 
 __device__ __forceinline__ int wave_excl_scan(int v, int *total)
 {
-    const int lane = threadIdx.x & 63;
-    int incl = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        int t = __shfl_up(incl, off, 64);
-        if (lane >= off) incl += t;
-    }
+    const int incl = wave_incl_scan(v);
     *total = __shfl(incl, 63, 64);
     return incl - v;
 }
