@@ -28,23 +28,42 @@ union Pack16 {           // 16 bytes seen as halves, dwords or one vector load
     uint32_t w[4];
 };
 
+// Wave-wide reductions with DPP moves (no LDS crossbar): an inclusive scan -- shifts by 1, 2, 4, 8
+// inside each row of 16 lanes, then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into
+// rows 2 and 3 -- leaves the result of all 64 lanes in lane 63, which is read back as a scalar.
+// Lanes without a source combine with the operation's identity.
+#define QUOTA_DPP_STEPS(STEP) \
+    STEP(0x111, 0xf) STEP(0x112, 0xf) STEP(0x114, 0xf) STEP(0x118, 0xf) STEP(0x142, 0xa) STEP(0x143, 0xc)
+
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-    return v;
+#define STEP(ctrl, rows)                                                                              \
+    v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), ctrl, \
+                                                            rows, 0xf, false)));
+    QUOTA_DPP_STEPS(STEP)
+#undef STEP
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ __forceinline__ double wave_sum(double v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+#define STEP(ctrl, rows)                                                                       \
+    {                                                                                          \
+        const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), ctrl, rows, 0xf, false); \
+        const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), ctrl, rows, 0xf, false); \
+        v += __hiloint2double(hi, lo);                                                         \
+    }
+    QUOTA_DPP_STEPS(STEP)
+#undef STEP
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 63),
+                            __builtin_amdgcn_readlane(__double2loint(v), 63));
 }
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+#define STEP(ctrl, rows) \
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, rows, 0xf, false));
+    QUOTA_DPP_STEPS(STEP)
+#undef STEP
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 // block-wide (blockDim.x = 64*NW) max of a float and sum of up to two doubles;
