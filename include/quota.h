@@ -192,6 +192,25 @@ int quota_attention_prefill_gqa(const void *q_f16, const void *khat_f16,
                                 float *cm_inter, float *cm_intra, void *ws,
                                 void *stream);
 
+/* For callers that cannot allocate device memory or carry a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): quota_attention_prefill_gqa with its two intermediates (row
+ * log-sum-exp, per-head column masses) in a device array that is part of the
+ * library image instead of `ws`.  Calls no allocating routine.  Same
+ * arguments, results and errors otherwise; additionally QUOTA_ERR_CAPACITY
+ * when B*H*N > QUOTA_ATTENTION_STATIC_MAX_ROWS (the array is 12 bytes per
+ * (sequence, head, token): 3 MiB, held by every GPU the library runs on until
+ * the process ends).  The first call on a device looks the array's address up
+ * (once per device; make that call outside graph capture).  All calls on one
+ * GPU share the array: calls that overlap on one GPU (different streams or
+ * threads) race; calls ordered on one stream do not. */
+#define QUOTA_ATTENTION_STATIC_MAX_ROWS 262144
+int quota_attention_prefill_static(const void *q_f16, const void *khat_f16,
+                                   const void *vhat_f16, int B, int N, int H,
+                                   int Hkv, int dh, int vis_begin, int Nv,
+                                   void *o_f16, float *cm_inter, float *cm_intra,
+                                   void *stream);
+
 /* ---- scoring (Eq. 6-8) and budgeted top-k (Eq. 5, Eq. 9) ---------------- */
 
 typedef struct quota_score_params {

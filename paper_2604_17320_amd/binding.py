@@ -176,6 +176,13 @@ def quota_attention_prefill_gqa(q, khat, vhat, B, N, H, Hkv, dh, vis_begin, Nv, 
            "quota_attention_prefill_gqa")
 
 
+def quota_attention_prefill_static(q, khat, vhat, B, N, H, Hkv, dh, vis_begin, Nv, o, cm_inter, cm_intra):
+    _check(lib().quota_attention_prefill_static(_ptr(q, torch.float16), _ptr(khat, torch.float16),
+                                                _ptr(vhat, torch.float16), B, N, H, Hkv, dh, vis_begin, Nv,
+                                                _ptr(o), _ptr(cm_inter), _ptr(cm_intra), _stream()),
+           "quota_attention_prefill_static")
+
+
 def quota_attention_workspace_bytes(B, N, H, dh):
     return lib().quota_attention_workspace_bytes(B, N, H, dh)
 

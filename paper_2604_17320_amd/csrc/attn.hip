@@ -373,6 +373,39 @@ extern "C" int quota_attention_prefill_gqa(const void *q_f16, const void *khat_f
     return QUOTA_OK;
 }
 
+// ---- the same call for callers that cannot allocate ---------------------------------------
+// The row log-sum-exp and the per-head column masses (the two intermediates the call above keeps
+// in the caller's workspace) live in a file-scope device array instead.  Host code never uses the
+// array's name as an address: each device's copy is looked up once with hipGetSymbolAddress, with
+// that device current, and the kernels receive the looked-up pointer like any other buffer.
+// Every element the cue pass and the head mean read has been written earlier in the same call,
+// so nothing needs clearing between calls.
+static __device__ __align__(256) float attn_scratch[3 * QUOTA_ATTENTION_STATIC_MAX_ROWS];
+
+namespace {
+constexpr int kMaxDevices = 64;
+float *attn_scratch_ptr[kMaxDevices];      // per device, null until the first call on it
+}
+
+extern "C" int quota_attention_prefill_static(const void *q_f16, const void *khat_f16,
+                                              const void *vhat_f16, int B, int N, int H, int Hkv,
+                                              int dh, int vis_begin, int Nv, void *o_f16,
+                                              float *cm_inter, float *cm_intra, void *stream)
+{
+    if (B <= 0 || N < 0 || H <= 0) return QUOTA_ERR_INVALID_ARG;
+    if ((long)B * H * N > (long)QUOTA_ATTENTION_STATIC_MAX_ROWS) return QUOTA_ERR_CAPACITY;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return QUOTA_ERR_HIP;
+    if (!attn_scratch_ptr[dev]) {
+        float *p = nullptr;
+        if (hipGetSymbolAddress((void **)&p, HIP_SYMBOL(attn_scratch)) != hipSuccess || !p)
+            return QUOTA_ERR_HIP;
+        attn_scratch_ptr[dev] = p;
+    }
+    return quota_attention_prefill_gqa(q_f16, khat_f16, vhat_f16, B, N, H, Hkv, dh, vis_begin, Nv,
+                                       o_f16, cm_inter, cm_intra, attn_scratch_ptr[dev], stream);
+}
+
 extern "C" int quota_attention_prefill(const void *q_f16, const void *khat_f16,
                                        const void *vhat_f16, int B, int N, int H, int dh,
                                        int vis_begin, int Nv, void *o_f16, float *cm_inter,
