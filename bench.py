@@ -190,7 +190,7 @@ def cpu_baseline(shape, stack, budgets, rope, sample_layers, seed):
     n, nv = shape.N, shape.Nv
     for K in budgets:
         rows_in.append((n, nv))
-        k = min(K, nv)
+        k = nv if K < 0 else min(K, nv)
         n, nv = n - nv + k, k
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     t_sum, r_sum = 0.0, 0

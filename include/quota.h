@@ -82,7 +82,7 @@ int quota_pack_weights(const int8_t *codes, const void *scales_f16,
  * q_packed uint8 [M][d/2]; scale fp32 [M].  Optional side outputs per row:
  * sumsq_opt = sum x^2 (m_mag^2) and ressq_opt = sum (code*scale - x)^2
  * (m_res^2), both accumulated in fp64 and rounded to fp32.
- * Requires d % 8 == 0, d <= 16384, ldx >= d and ldx % 8 == 0. */
+ * Requires d % 8 == 0, d <= 32768, ldx >= d and ldx % 8 == 0. */
 int quota_quantize_act(const void *x_f16, int M, int d, int ldx,
                        uint8_t *q_packed, float *scale, float *sumsq_opt,
                        float *ressq_opt, void *stream);
@@ -103,7 +103,7 @@ int quota_rmsnorm_quantize_act(const void *x_f16, int M, int d, int ldx,
  * z = fp16(silu(gate) * up) with gate = gu[:, 0:F], up = gu[:, F:2F]
  * (gu fp16 [M][2F] dense), then the quantizer applied to z.  z_opt receives
  * z; z_inject_opt, when not null, replaces the computed z (parity harness).
- * Requires F % 8 == 0 and F <= 16384. */
+ * Requires F % 8 == 0 and F <= 32768. */
 int quota_silu_mul_quantize_act(const void *gu_f16, int M, int F,
                                 uint8_t *q_packed, float *scale, void *z_opt,
                                 const void *z_inject_opt, void *stream);
@@ -121,6 +121,14 @@ int quota_w4a4_gemm(const uint8_t *qa, const float *sa, int M,
                     const quota_weights *W, void *y_f16, int ldy,
                     const void *residual_opt, int ldr, int32_t *acc_i32_opt,
                     void *stream);
+
+/* Pins the GEMM kernel variant that quota_w4a4_gemm and the layer calls use
+ * from now on (process-wide; for tests and tuning): -1 = chosen per launch
+ * (default); 0..4 = the workgroup-tiled kernels 64x256, 64x128, 32x128,
+ * 32x128 deep prefetch, 64x128 lean.  Launches a variant cannot take (at
+ * most 16 rows, the int32 output, the 256-column tile with the fused QKV
+ * epilogue) ignore the pin.  QUOTA_ERR_INVALID_ARG for other values. */
+int quota_set_gemm_variant(int variant);
 
 /* ---- RoPE + 4-bit KV quantization (quantized KV cache) ------------------ */
 
@@ -307,6 +315,11 @@ typedef struct quota_taps {
 
 size_t quota_prefill_workspace_bytes(const quota_layer *L, int B, int N);
 
+/* K_l value for a layer that is not a pruning candidate (the recipe prunes at
+ * the candidate layers only): no cue pass, no score, no top-k; every token is
+ * kept. */
+#define QUOTA_KEEP_ALL (-1)
+
 /* One decoder layer of the deployed low-bit forward pass (Method overview;
  * Eq. 5-9 and the compaction paragraph): RMSNorm + int4 activations + W4A4
  * QKV, RoPE, 4-bit K/V for all N tokens, causal attention over the 4-bit
@@ -314,9 +327,16 @@ size_t quota_prefill_workspace_bytes(const quota_layer *L, int B, int N);
  * compaction: kept rows of the hidden state and positions move on, their 4-bit
  * K/V rows are appended to `cache` (this layer's cache), and the output
  * projection and SwiGLU FFN (all token-wise) run on the kept rows only.
- * K_l >= Nv keeps every token.  ws: quota_prefill_workspace_bytes bytes.
- * Errors: as the calls above; QUOTA_ERR_CAPACITY when the cache cannot take
- * n_keep more rows. */
+ * K_l >= Nv keeps every token but still scores them; K_l = QUOTA_KEEP_ALL marks
+ * a layer outside the candidate set: the cue pass, the score and the top-k are
+ * skipped.  ws: quota_prefill_workspace_bytes bytes.
+ * Every limit of the steps is checked before the first launch, and the
+ * descriptors (cache->len, st->N, st->Nv) move only after the last one, so a
+ * call that returns an error has enqueued nothing and changed nothing:
+ * QUOTA_ERR_SHAPE for dh not 64 / 128, H % Hkv != 0, F % 32 != 0, d > 16384,
+ * F > 32768, more than 3072 visual tokens in a candidate layer, weight shapes
+ * that do not fit the layer or the packer; QUOTA_ERR_CAPACITY when the cache
+ * cannot take n_keep more rows. */
 int quota_prefill_layer(const quota_layer *L, quota_state *st, int K_l,
                         const quota_score_params *p, quota_kv_cache *cache,
                         const quota_taps *taps_opt, void *ws, void *stream);
@@ -381,7 +401,10 @@ size_t quota_decode_workspace_bytes(const quota_layer *L, int B);
  * x fp16 [B][d], pos int32 [B], x_out fp16 [B][d] (all device); B must equal
  * cache->B.  taps_opt: qkv, q_rot, o, x1, gu, z dumps and inject_o / inject_z
  * are honoured (parity harness).  ws: quota_decode_workspace_bytes bytes.
- * QUOTA_ERR_CAPACITY when the cache is full (nothing is written). */
+ * Checked before the first launch: QUOTA_ERR_CAPACITY when the cache is full,
+ * QUOTA_ERR_SHAPE when it would hold more than 8192 rows or for the layer
+ * shapes quota_prefill_layer rejects; cache->len is advanced after the last
+ * launch, so an error leaves the cache as it was. */
 int quota_decode_layer(const quota_layer *L, const void *x_f16,
                        const int32_t *pos, int B, quota_kv_cache *cache,
                        void *x_out_f16, const quota_taps *taps_opt, void *ws,

@@ -16,6 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libquota.so")
 
 OK = 0
+KEEP_ALL = -1          # K_l of a layer outside the candidate set (QUOTA_KEEP_ALL)
 ERR_NULL, ERR_INVALID_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_HIP = -1, -2, -3, -4, -5
 
 
@@ -153,6 +154,10 @@ def quota_w4a4_gemm(qa, sa, M, W: Weights, y, ldy, residual=None, ldr=0, acc_i32
     _check(lib().quota_w4a4_gemm(_ptr(qa, torch.uint8), _ptr(sa, torch.float32), M, C.byref(W),
                                  _ptr(y), ldy, _ptr(residual), ldr, _ptr(acc_i32), _stream()),
            "quota_w4a4_gemm")
+
+
+def quota_set_gemm_variant(variant: int):
+    _check(lib().quota_set_gemm_variant(int(variant)), "quota_set_gemm_variant")
 
 
 def quota_rope_kv_quant(qkv, M, H, dh, pos, cosT, sinT, n_pos, q_rot, khat, vhat, k_codes, k_scales,

@@ -8,7 +8,7 @@
 
 namespace {
 
-constexpr int DEC_LMAX = 8192;      // cached rows one workgroup can softmax over (scores live in LDS)
+constexpr int DEC_LMAX = QUOTA_MAX_DECODE_ROWS;      // cached rows one workgroup can softmax over (scores live in LDS)
 
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 
@@ -164,8 +164,7 @@ int quota_internal_kv_append_rows(int d, const uint8_t *skc, const void *sks, co
         c->capacity, c->len, (uint32_t *)c->k_codes, (f16 *)c->k_scales, (uint32_t *)c->v_codes,
         (f16 *)c->v_scales);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
-    c->len += 1;
-    return QUOTA_OK;
+    return QUOTA_OK;         // the caller advances cache->len
 }
 
 extern "C" int quota_attention_decode_gqa(const void *q_f16, int Hq, const quota_kv_cache *cache,

@@ -21,34 +21,13 @@
 // (high nibbles) int8 vectors; lane half h of k-step ks takes the even (ks
 // even) or odd (ks odd) vector of chunk 2*h + ks/2.
 #include "common.h"
-#include <cstdlib>
 #include "internal.h"
 #include "ropequant.h"
+#include "gemm_common.h"
 
 namespace {
 
 constexpr int AROW = 9;     // LDS row stride in 16-byte units: 8 data + 1 pad (conflict-free b128)
-
-__device__ __forceinline__ void unpack16(const uint4 &v, uint4 &lo, uint4 &hi)
-{
-    lo.x = (v.x << 4) & 0xF0F0F0F0u; hi.x = v.x & 0xF0F0F0F0u;
-    lo.y = (v.y << 4) & 0xF0F0F0F0u; hi.y = v.y & 0xF0F0F0F0u;
-    lo.z = (v.z << 4) & 0xF0F0F0F0u; hi.z = v.z & 0xF0F0F0F0u;
-    lo.w = (v.w << 4) & 0xF0F0F0F0u; hi.w = v.w & 0xF0F0F0F0u;
-}
-__device__ __forceinline__ i32x4 as_i32x4(const uint4 &t)
-{
-    return i32x4{(int)t.x, (int)t.y, (int)t.z, (int)t.w};
-}
-
-// XCD-aware tile id: consecutive dispatch ids go round-robin over the 8 XCDs
-// (each with its own L2), so give each XCD a contiguous range of tiles.
-__device__ __forceinline__ int xcd_remap(int pid, int total)
-{
-    int x = pid & 7, idx = pid >> 3;
-    int per = total >> 3, rem = total & 7;
-    return x * per + (x < rem ? x : rem) + idx;
-}
 
 // Workgroup tile (32*TM) x (128*TN); wave w owns columns [w*32*TN, (w+1)*32*TN).
 // CH > 0: the LDS stage holds CH groups of activations, so the workgroup meets at a
@@ -530,6 +509,15 @@ int launch(int kernel_id, const uint8_t *qa, const float *sa, int M, const quota
 // pipeline, registers capped so that three workgroups fit on a CU) takes the launches that
 // would need a second round of the pipelined one.  `allow_wide` = false leaves the
 // 256-column tile out.
+static int g_gemm_variant = -1;      // -1: chosen per launch; else pinned by quota_set_gemm_variant
+
+extern "C" int quota_set_gemm_variant(int variant)
+{
+    if (variant < -1 || variant > 4) return QUOTA_ERR_INVALID_ARG;
+    g_gemm_variant = variant;
+    return QUOTA_OK;
+}
+
 static int choose_tile(int M, int N, int K, bool allow_wide)
 {
     struct Tile { int bm, bn, R; float c0, u[3], f0, f1; };
@@ -540,12 +528,7 @@ static int choose_tile(int M, int N, int K, bool allow_wide)
         {32, 128, 2, 4.0f, {0.27f, 0.46f, 0.0f}, 0.0f, 1.45f},      // <1,1,8,4> pipelined, deep prefetch
         {64, 128, 3, 6.0f, {0.53f, 0.75f, 1.06f}, 0.0f, 1.3f},      // <2,1,3,0>, three workgroups per CU
     };
-    // QUOTA_GEMM_TILE=0..4 in the environment pins the choice (tests cover every instantiation
-    // that way; also handy for tuning)
-    if (const char *e = getenv("QUOTA_GEMM_TILE")) {
-        const int v = atoi(e);
-        if (v >= (allow_wide ? 0 : 1) && v < 5) return v;
-    }
+    if (g_gemm_variant >= (allow_wide ? 0 : 1) && g_gemm_variant < 5) return g_gemm_variant;
     const int G = (K + QUOTA_GROUP_W - 1) / QUOTA_GROUP_W;
     int best = -1;
     float best_t = 0.0f;

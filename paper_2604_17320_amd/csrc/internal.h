@@ -25,7 +25,7 @@ int quota_internal_attention(const void *q_f16, const void *khat_f16, const void
 
 struct quota_compact_args {
     int B, N, vis_begin, Nv, k_keep, n_keep, d, dkv;      // dkv: width of a K or V row (Hkv * dh)
-    const int32_t *keep_idx;
+    const int32_t *keep_idx;              // null: the first k_keep visual tokens (k_keep = Nv: all of them)
     const void *x, *o;
     const int32_t *pos;
     const void *skc, *sks, *svc, *svs;     // staged 4-bit K/V of all N rows
@@ -35,13 +35,14 @@ struct quota_compact_args {
     int32_t *pos_out, *rows_out;
     quota_kv_cache *cache;
 };
+// Appends at row cache->len but does not advance it.
 int quota_internal_compact(const quota_compact_args *a, hipStream_t st);
 
 int quota_internal_vector_metrics(const void *v_f16, int B, int Nv, int d, int ldv, long stride_b,
                                   float *sumsq, float *ressq, hipStream_t st);
 
 // Moves the B staged (dense) 4-bit K/V rows of a decode step to row cache->len of each
-// sequence and advances cache->len by 1.  QUOTA_ERR_CAPACITY if the cache is full.
+// sequence (the caller advances cache->len).  QUOTA_ERR_CAPACITY if the cache is full.
 int quota_internal_kv_append_rows(int d, const uint8_t *skc, const void *sks, const uint8_t *svc,
                                   const void *svs, quota_kv_cache *cache, hipStream_t st);
 
@@ -63,3 +64,11 @@ int quota_internal_rope_kv_quant(const void *qkv_f16, int M, int H, int Hkv, int
                                  const float *cosT, const float *sinT, int n_pos, void *q_rot_f16,
                                  void *khat_f16, void *vhat_f16, uint8_t *k_codes, void *k_scales,
                                  uint8_t *v_codes, void *v_scales, hipStream_t st);
+
+
+// Limits that the kernels behind the layer calls enforce, for the up-front checks of the layer
+// calls (a call that returns an error must not have enqueued anything).
+#define QUOTA_MAX_SCORED_TOKENS 3072      // visual tokens per sequence the score / top-k kernel holds in LDS
+#define QUOTA_MAX_DECODE_ROWS 8192        // cached rows per sequence the decode attention softmaxes over
+#define QUOTA_MAX_MODEL_WIDTH 16384       // d: the compaction gather keeps a row in registers
+#define QUOTA_MAX_ROW_COLS 32768          // widest row of the row quantizers (the FFN width F)

@@ -176,7 +176,7 @@ __global__ __launch_bounds__(256) void compact_rows_kernel(
     const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     int src;
     if (j < vis_begin) src = j;
-    else if (j < vis_begin + k_keep) src = vis_begin + keep_idx[(size_t)b * k_keep + (j - vis_begin)];
+    else if (j < vis_begin + k_keep) src = vis_begin + (keep_idx ? keep_idx[(size_t)b * k_keep + (j - vis_begin)] : j - vis_begin);
     else src = j - k_keep + Nv;
     src = min(max(src, 0), N - 1);
     const size_t srow = (size_t)b * N + src, drow = (size_t)b * n_keep + j;
@@ -244,13 +244,13 @@ int quota_internal_compact(const quota_compact_args *a, hipStream_t st)
 {
     quota_kv_cache *c = a->cache;
     if (c->len + a->n_keep > c->capacity) return QUOTA_ERR_CAPACITY;
-    if (a->d % 8 != 0 || a->d > ROW_MAXCHUNK * ROW_THREADS * 8 || a->dkv > a->d || a->dkv < 64 ||
+    if (a->d % 8 != 0 || a->d > 8 * ROW_THREADS * 8 || a->dkv > a->d || a->dkv < 64 ||
         a->dkv / 64 > ROW_THREADS)
         return QUOTA_ERR_SHAPE;
     if (a->n_keep == 0) return QUOTA_OK;
     const double rows = (double)a->n_keep * a->B, dd = a->d, dk = a->dkv;
     ProfScope prof(QUOTA_K_COMPACT_ROWS, 0, rows * (2 * (4 * dd + dk + dk / 16) + 8), st);
-    auto kernel = a->d <= 4096 ? compact_rows_kernel<2> : compact_rows_kernel<ROW_MAXCHUNK>;
+    auto kernel = a->d <= 4096 ? compact_rows_kernel<2> : compact_rows_kernel<8>;
     kernel<<<dim3(a->n_keep, a->B), dim3(256), 0, st>>>(
         a->N, a->vis_begin, a->Nv, a->k_keep, a->n_keep, a->keep_idx, a->d, a->dkv, (const f16 *)a->x,
         (const f16 *)a->o, a->pos, (const uint32_t *)a->skc, (const f16 *)a->sks,
@@ -258,8 +258,7 @@ int quota_internal_compact(const quota_compact_args *a, hipStream_t st)
         a->rows_out, c->capacity, c->len, (uint32_t *)c->k_codes, (f16 *)c->k_scales,
         (uint32_t *)c->v_codes, (f16 *)c->v_scales);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
-    c->len += a->n_keep;
-    return QUOTA_OK;
+    return QUOTA_OK;         // the caller advances cache->len once the whole layer is enqueued
 }
 
 int quota_internal_rope_kv_quant(const void *qkv_f16, int M, int H, int Hkv, int dh, const int32_t *pos,

@@ -114,10 +114,7 @@ static int qkv_rope_kv_quant(const quota_layer *L, const LayerWs &w, int M, cons
         qe.code_row_stride = append_to->capacity; qe.code_row_offset = append_to->len;
     }
     int rc = quota_internal_w4a4_gemm_qkv(w.qa, w.sa, M, &L->qkv, want_qkv ? w.qkv : nullptr, &qe, st);
-    if (rc != QUOTA_ERR_SHAPE) {
-        if (rc == QUOTA_OK && append_to) append_to->len += 1;
-        return rc;
-    }
+    if (rc != QUOTA_ERR_SHAPE) return rc;
     TRY(quota_w4a4_gemm(w.qa, w.sa, M, &L->qkv, w.qkv, d + 2 * dkv, nullptr, 0, nullptr, st));
     TRY(quota_internal_rope_kv_quant(w.qkv, M, L->H, Hkv, L->dh, pos, L->cosT, L->sinT, L->n_pos, w.q_rot,
                                      w.khat, w.vhat, w.skc, w.sks, w.svc, w.svs, st));
@@ -130,22 +127,43 @@ extern "C" size_t quota_prefill_workspace_bytes(const quota_layer *L, int B, int
     return carve(nullptr, B, N, L->H, kv_heads(L), L->dh, L->F).bytes;
 }
 
+// Everything a later step of a layer call would reject, checked before the first launch.
+static int check_layer(const quota_layer *L, int B, const quota_kv_cache *cache)
+{
+    if (!L->gamma1 || !L->gamma2 || !L->cosT || !L->sinT) return QUOTA_ERR_NULL;
+    if (!cache->k_codes || !cache->k_scales || !cache->v_codes || !cache->v_scales) return QUOTA_ERR_NULL;
+    const quota_weights *ws[4] = {&L->qkv, &L->o, &L->gu, &L->down};
+    for (const quota_weights *w : ws)
+        if (!w->packed || !w->scales) return QUOTA_ERR_NULL;
+    const int H = L->H, dh = L->dh, F = L->F;
+    if (B <= 0 || H <= 0 || F <= 0 || L->n_pos <= 0 || !(L->eps >= 0.0f) || cache->len < 0 || cache->capacity < 0)
+        return QUOTA_ERR_INVALID_ARG;
+    const int d = H * dh, Hkv = kv_heads(L), dkv = Hkv * dh;
+    if ((dh != 64 && dh != 128) || Hkv <= 0 || H % Hkv != 0 || F % 32 != 0 || d > QUOTA_MAX_MODEL_WIDTH ||
+        F > QUOTA_MAX_ROW_COLS || dkv / 64 > 256)
+        return QUOTA_ERR_SHAPE;
+    if (L->qkv.N != d + 2 * dkv || L->qkv.K != d || L->o.N != d || L->o.K != d || L->gu.N != 2 * F ||
+        L->gu.K != d || L->down.N != d || L->down.K != F)
+        return QUOTA_ERR_SHAPE;
+    for (const quota_weights *w : ws)
+        if (w->N % 64 != 0 || w->K % 32 != 0) return QUOTA_ERR_SHAPE;
+    if (cache->B != B || cache->H != Hkv || cache->dh != dh) return QUOTA_ERR_SHAPE;
+    return QUOTA_OK;
+}
+
 extern "C" int quota_prefill_layer(const quota_layer *L, quota_state *s, int K_l,
                                    const quota_score_params *p, quota_kv_cache *cache,
                                    const quota_taps *taps, void *ws, void *stream)
 {
-    if (!L || !s || !p || !cache || !ws || !s->x || !s->pos || !s->x_out || !s->pos_out ||
-        !L->gamma1 || !L->gamma2 || !L->cosT || !L->sinT)
-        return QUOTA_ERR_NULL;
+    if (!L || !s || !p || !cache || !ws || !s->x || !s->pos || !s->x_out || !s->pos_out) return QUOTA_ERR_NULL;
     const int B = s->B, N = s->N, vb = s->vis_begin, Nv = s->Nv, H = L->H, dh = L->dh, F = L->F;
-    if (B <= 0 || N <= 0 || vb < 0 || Nv < 0 || vb + Nv > N || K_l < 0) return QUOTA_ERR_INVALID_ARG;
+    TRY(check_layer(L, B, cache));
+    if (N <= 0 || vb < 0 || Nv < 0 || vb + Nv > N || K_l < QUOTA_KEEP_ALL) return QUOTA_ERR_INVALID_ARG;
+    if (p->pct_lo < 0 || p->pct_hi > 100 || p->pct_lo > p->pct_hi) return QUOTA_ERR_INVALID_ARG;
+    const bool candidate = K_l != QUOTA_KEEP_ALL;        // this layer scores and prunes
+    if (candidate && Nv > QUOTA_MAX_SCORED_TOKENS) return QUOTA_ERR_SHAPE;
     const int d = H * dh, Hkv = kv_heads(L), dkv = Hkv * dh;
-    if ((dh != 64 && dh != 128) || F % 32 != 0 || H % Hkv != 0) return QUOTA_ERR_SHAPE;
-    if (L->qkv.N != d + 2 * dkv || L->qkv.K != d || L->o.N != d || L->o.K != d || L->gu.N != 2 * F ||
-        L->gu.K != d || L->down.N != d || L->down.K != F)
-        return QUOTA_ERR_SHAPE;
-    if (cache->B != B || cache->H != Hkv || cache->dh != dh) return QUOTA_ERR_SHAPE;
-    const int k_keep = K_l < Nv ? K_l : Nv;
+    const int k_keep = !candidate || K_l > Nv ? Nv : K_l;
     const int n_keep = N - Nv + k_keep;
     if (cache->len + n_keep > cache->capacity) return QUOTA_ERR_CAPACITY;
 
@@ -154,22 +172,24 @@ extern "C" int quota_prefill_layer(const quota_layer *L, quota_state *s, int K_l
     const int M = B * N, Mk = B * n_keep;
     static const quota_taps no_taps = {};
     const quota_taps *t = taps ? taps : &no_taps;
+    const bool score = candidate && Nv > 0;
 
-    // attention half on every token that entered the layer
-    TRY(quota_rmsnorm_quantize_act(s->x, M, d, d, L->gamma1, L->eps, w.qa, w.sa, w.sumsq, w.ressq,
-                                   nullptr, st));
+    // attention half on every token that entered the layer (the two vector cues of Eq. 6 are side
+    // outputs of the first quantizer, taken only where they are used)
+    TRY(quota_rmsnorm_quantize_act(s->x, M, d, d, L->gamma1, L->eps, w.qa, w.sa, score ? w.sumsq : nullptr,
+                                   score ? w.ressq : nullptr, nullptr, st));
     TRY(qkv_rope_kv_quant(L, w, M, s->pos, t->qkv != nullptr, st));
     TRY(dump(t->qkv, w.qkv, (size_t)M * (d + 2 * dkv) * 2, st));
     TRY(dump(t->q_rot, w.q_rot, (size_t)M * d * 2, st));
     const float *partial = nullptr;     // per-head column masses; their head mean is taken by the score kernel
-    TRY(quota_internal_attention(w.q_rot, w.khat, w.vhat, B, N, H, Hkv, dh, vb, Nv, w.o, true, w.attn_ws,
+    TRY(quota_internal_attention(w.q_rot, w.khat, w.vhat, B, N, H, Hkv, dh, vb, Nv, w.o, score, w.attn_ws,
                                  &partial, st));
     TRY(dump(t->o, w.o, (size_t)M * d * 2, st));
     const f16 *o_used = t->inject_o ? (const f16 *)t->inject_o : w.o;
     const bool inject_cm = t->inject_cm_inter && t->inject_cm_intra;
 
-    // Eq. 6-9: cues -> G -> fused score -> top-K_l over the visual tokens
-    if (Nv > 0) {
+    // Eq. 6-9: cues -> G -> fused score -> top-K_l over the visual tokens (candidate layers only)
+    if (score) {
         if (inject_cm) {
             // the library's own cues are still produced for the dump taps
             if (t->cm_inter || t->cm_intra) {
@@ -201,7 +221,7 @@ extern "C" int quota_prefill_layer(const quota_layer *L, quota_state *s, int K_l
     // attention-output rows leave the gather already quantized for the output projection
     quota_compact_args ca;
     ca.B = B; ca.N = N; ca.vis_begin = vb; ca.Nv = Nv; ca.k_keep = k_keep; ca.n_keep = n_keep;
-    ca.d = d; ca.dkv = dkv; ca.keep_idx = w.keep_idx; ca.x = s->x; ca.o = o_used; ca.pos = s->pos;
+    ca.d = d; ca.dkv = dkv; ca.keep_idx = score ? w.keep_idx : nullptr; ca.x = s->x; ca.o = o_used; ca.pos = s->pos;
     ca.skc = w.skc; ca.sks = w.sks; ca.svc = w.svc; ca.svs = w.svs;
     ca.x_out = w.x_keep; ca.o_out = nullptr; ca.oq_out = w.qa; ca.os_out = w.sa;
     ca.pos_out = s->pos_out; ca.rows_out = w.rows;
@@ -220,6 +240,8 @@ extern "C" int quota_prefill_layer(const quota_layer *L, quota_state *s, int K_l
         TRY(quota_silu_mul_quantize_act(w.gu, Mk, F, w.qa, w.sa, t->z, t->inject_z, st));
         TRY(quota_w4a4_gemm(w.qa, w.sa, Mk, &L->down, s->x_out, d, w.x1, d, nullptr, st));
     }
+    // the descriptors move only now that every step has been enqueued
+    cache->len += n_keep;
     s->N = n_keep;
     s->Nv = k_keep;
     return QUOTA_OK;
@@ -234,18 +256,11 @@ extern "C" int quota_decode_layer(const quota_layer *L, const void *x_f16, const
                                   quota_kv_cache *cache, void *x_out_f16, const quota_taps *taps,
                                   void *ws, void *stream)
 {
-    if (!L || !x_f16 || !pos || !cache || !x_out_f16 || !ws || !L->gamma1 || !L->gamma2 || !L->cosT ||
-        !L->sinT)
-        return QUOTA_ERR_NULL;
+    if (!L || !x_f16 || !pos || !cache || !x_out_f16 || !ws) return QUOTA_ERR_NULL;
+    TRY(check_layer(L, B, cache));
     const int H = L->H, dh = L->dh, F = L->F, d = H * dh, Hkv = kv_heads(L), dkv = Hkv * dh;
-    if (B <= 0) return QUOTA_ERR_INVALID_ARG;
-    if ((dh != 64 && dh != 128) || F % 32 != 0 || H % Hkv != 0) return QUOTA_ERR_SHAPE;
-    if (L->qkv.N != d + 2 * dkv || L->qkv.K != d || L->o.N != d || L->o.K != d || L->gu.N != 2 * F ||
-        L->gu.K != d || L->down.N != d || L->down.K != F)
-        return QUOTA_ERR_SHAPE;
-    if (cache->B != B || cache->H != Hkv || cache->dh != dh) return QUOTA_ERR_SHAPE;
-    if (cache->len < 0) return QUOTA_ERR_INVALID_ARG;
     if (cache->len + 1 > cache->capacity) return QUOTA_ERR_CAPACITY;
+    if (cache->len + 1 > QUOTA_MAX_DECODE_ROWS) return QUOTA_ERR_SHAPE;
 
     hipStream_t st = (hipStream_t)stream;
     LayerWs w = carve(ws, B, 1, H, Hkv, dh, F);
@@ -259,7 +274,9 @@ extern "C" int quota_decode_layer(const quota_layer *L, const void *x_f16, const
     TRY(qkv_rope_kv_quant(L, w, B, pos, t->qkv != nullptr, st, cache));
     TRY(dump(t->qkv, w.qkv, (size_t)B * (d + 2 * dkv) * 2, st));
     TRY(dump(t->q_rot, w.q_rot, (size_t)B * d * 2, st));
-    TRY(quota_attention_decode_gqa(w.q_rot, H, cache, w.o, st));
+    quota_kv_cache grown = *cache;      // what the attention reads: the row just written included
+    grown.len += 1;
+    TRY(quota_attention_decode_gqa(w.q_rot, H, &grown, w.o, st));
     TRY(dump(t->o, w.o, (size_t)B * d * 2, st));
     const f16 *o_used = t->inject_o ? (const f16 *)t->inject_o : w.o;
 
@@ -272,5 +289,6 @@ extern "C" int quota_decode_layer(const quota_layer *L, const void *x_f16, const
     TRY(dump(t->gu, w.gu, (size_t)B * 2 * F * 2, st));
     TRY(quota_silu_mul_quantize_act(w.gu, B, F, w.qa, w.sa, t->z, t->inject_z, st));
     TRY(quota_w4a4_gemm(w.qa, w.sa, B, &L->down, x_out_f16, d, w.x1, d, nullptr, st));
+    cache->len += 1;                    // only now that every step has been enqueued
     return QUOTA_OK;
 }

@@ -32,10 +32,19 @@ extern "C" int quota_profile_begin(int max_launches)
     p.kid = (int *)calloc(max_launches, sizeof(int));
     p.ops = (double *)calloc(max_launches, sizeof(double));
     p.bytes = (double *)calloc(max_launches, sizeof(double));
-    if (!p.ev || !p.kid || !p.ops || !p.bytes) return QUOTA_ERR_INVALID_ARG;
-    p.cap = max_launches;
+    if (!p.ev || !p.kid || !p.ops || !p.bytes) {
+        free(p.ev); free(p.kid); free(p.ops); free(p.bytes);
+        p = QuotaProfiler();
+        return QUOTA_ERR_INVALID_ARG;
+    }
     for (int i = 0; i < 2 * max_launches; ++i)
-        if (hipEventCreate(&p.ev[i]) != hipSuccess) { p.cap = i / 2; prof_free(); return QUOTA_ERR_HIP; }
+        if (hipEventCreate(&p.ev[i]) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(p.ev[j]);      // exactly the events created
+            free(p.ev); free(p.kid); free(p.ops); free(p.bytes);
+            p = QuotaProfiler();
+            return QUOTA_ERR_HIP;
+        }
+    p.cap = max_launches;
     p.used = 0;
     p.on = true;
     return QUOTA_OK;

@@ -317,13 +317,16 @@ extern "C" int quota_quantize_act(const void *x_f16, int M, int d, int ldx, uint
     const f16 *x = (const f16 *)x_f16;
     uint32_t *q = (uint32_t *)q_packed;
     const bool few = (d >> 3) <= 2 * (small ? 64 : 256);      // two chunks per thread are enough
+    const bool many = d > 16384;                              // sixteen chunks per thread
 #define QUOTA_LAUNCH_Q(MET, GRP, NCH) \
     quantize_act_kernel<MET, GRP, NCH><<<grid, blk, 0, st>>>(x, M, d, ldx, M, 0, q, scale, sumsq_opt, ressq_opt)
     if (metrics) {
         if (small) { if (few) QUOTA_LAUNCH_Q(true, 64, 2); else QUOTA_LAUNCH_Q(true, 64, 8); }
+        else if (many) QUOTA_LAUNCH_Q(true, 256, 16);
         else { if (few) QUOTA_LAUNCH_Q(true, 256, 2); else QUOTA_LAUNCH_Q(true, 256, 8); }
     } else {
         if (small) { if (few) QUOTA_LAUNCH_Q(false, 64, 2); else QUOTA_LAUNCH_Q(false, 64, 8); }
+        else if (many) QUOTA_LAUNCH_Q(false, 256, 16);
         else { if (few) QUOTA_LAUNCH_Q(false, 256, 2); else QUOTA_LAUNCH_Q(false, 256, 8); }
     }
 #undef QUOTA_LAUNCH_Q
@@ -349,14 +352,17 @@ extern "C" int quota_rmsnorm_quantize_act(const void *x_f16, int M, int d, int l
     uint32_t *q = (uint32_t *)q_packed;
     f16 *h = (f16 *)h_opt;
     const bool few = (d >> 3) <= 2 * (small ? 64 : 256);      // two chunks per thread are enough
+    const bool many = d > 16384;                              // sixteen chunks per thread
 #define QUOTA_LAUNCH_R(MET, GRP, NCH)                                                                  \
     rmsnorm_quantize_act_kernel<MET, GRP, NCH><<<grid, blk, 0, st>>>(x, M, d, ldx, gamma, eps, q, scale, \
                                                                      sumsq_opt, ressq_opt, h)
     if (metrics) {
         if (small) { if (few) QUOTA_LAUNCH_R(true, 64, 2); else QUOTA_LAUNCH_R(true, 64, 8); }
+        else if (many) QUOTA_LAUNCH_R(true, 256, 16);
         else { if (few) QUOTA_LAUNCH_R(true, 256, 2); else QUOTA_LAUNCH_R(true, 256, 8); }
     } else {
         if (small) { if (few) QUOTA_LAUNCH_R(false, 64, 2); else QUOTA_LAUNCH_R(false, 64, 8); }
+        else if (many) QUOTA_LAUNCH_R(false, 256, 16);
         else { if (few) QUOTA_LAUNCH_R(false, 256, 2); else QUOTA_LAUNCH_R(false, 256, 8); }
     }
 #undef QUOTA_LAUNCH_R
@@ -375,10 +381,12 @@ extern "C" int quota_silu_mul_quantize_act(const void *gu_f16, int M, int F, uin
     const bool small = F <= 4096 && M >= ROW_WAVE_MIN_ROWS;
     const dim3 grid(small ? (M + 3) / 4 : M), blk(ROW_THREADS);
     const bool few = (F >> 3) <= 2 * (small ? 64 : 256);
+    const bool many = F > 16384;          // sixteen chunks per thread, loaded chunk by chunk
 #define QUOTA_LAUNCH_S(GRP, NCH, EARLY)                                                               \
     silu_mul_quantize_act_kernel<GRP, NCH, EARLY><<<grid, blk, 0, (hipStream_t)stream>>>(             \
         (const f16 *)gu_f16, M, F, (uint32_t *)q_packed, scale, (f16 *)z_opt, (const f16 *)z_inject_opt)
-    if (M >= ROW_WAVE_MIN_ROWS) {
+    if (many) QUOTA_LAUNCH_S(256, 16, false);
+    else if (M >= ROW_WAVE_MIN_ROWS) {
         if (small) { if (few) QUOTA_LAUNCH_S(64, 2, false); else QUOTA_LAUNCH_S(64, 8, false); }
         else { if (few) QUOTA_LAUNCH_S(256, 2, false); else QUOTA_LAUNCH_S(256, 8, false); }
     } else {
@@ -408,6 +416,7 @@ int quota_internal_vector_metrics(const void *v_f16, int B, int Nv, int d, int l
     quantize_act_kernel<true, GRP, NCH><<<grid, blk, 0, st>>>((const f16 *)v_f16, B * Nv, d, ldv, Nv, stride_b, \
                                                               nullptr, nullptr, sumsq, ressq)
     if (small) { if (few) QUOTA_LAUNCH_V(64, 2); else QUOTA_LAUNCH_V(64, 8); }
+    else if (d > 16384) QUOTA_LAUNCH_V(256, 16);
     else { if (few) QUOTA_LAUNCH_V(256, 2); else QUOTA_LAUNCH_V(256, 8); }
 #undef QUOTA_LAUNCH_V
     QUOTA_RETURN_IF_LAUNCH_FAILED();

@@ -5,8 +5,8 @@
 #include "common.h"
 
 #define ROW_THREADS 256
-#define ROW_MAXCHUNK 8   // workgroup-per-row kernels: 8 chunks * 8 halves * 256 threads = 16384 columns
-#define ROW_MAXCOLS 16384
+#define ROW_MAXCHUNK 16  // workgroup-per-row kernels: 16 chunks * 8 halves * 256 threads = 32768 columns
+#define ROW_MAXCOLS 32768
 
 // final phase shared by the row kernels: quantize the cached row `v` with absmax `a`, store the
 // packed codes, return this thread's share of the residual sum of squares.

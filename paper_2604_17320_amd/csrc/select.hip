@@ -10,7 +10,7 @@
 
 namespace {
 
-constexpr int MAXV = 3072;
+constexpr int MAXV = QUOTA_MAX_SCORED_TOKENS;
 
 // ascending uint32 order == ascending float order; -0 is folded onto +0
 __device__ __forceinline__ uint32_t float_key(float f)

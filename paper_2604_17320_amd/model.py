@@ -127,7 +127,7 @@ class PrefillStack:
         n, nv = N, Nv
         self.n_keep = []
         for K in budgets:
-            k = min(K, nv)
+            k = nv if K < 0 else min(K, nv)      # K < 0 (qb.KEEP_ALL): not a candidate layer, nothing pruned
             n = n - nv + k
             nv = k
             self.n_keep.append(n)

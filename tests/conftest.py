@@ -15,3 +15,12 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture
+def pinned_gemm():
+    """Pins the GEMM kernel variant for one test (quota_set_gemm_variant) and restores the automatic
+    choice afterwards."""
+    from paper_2604_17320_amd import binding
+    yield binding.quota_set_gemm_variant
+    binding.quota_set_gemm_variant(-1)

@@ -100,3 +100,70 @@ def test_recipe_matches_the_oracle():
         with pytest.raises(binding.QuotaError) as e:
             binding.quota_make_recipe(**bad)
         assert e.value.code == binding.ERR_INVALID_ARG
+
+
+def _fake_layer(binding, H=32, dh=128, F=11008, Hkv=0, null_weights=False):
+    """A layer descriptor whose pointers are never dereferenced: every call below must be rejected by
+    the host-side checks, before any device work."""
+    d, hk = H * dh, (Hkv or H)
+    P = 0 if null_weights else 0x1000
+    W = lambda n, k: binding.Weights(n, k, P, P)
+    return binding.Layer(H, dh, F, 1e-5, 0x1000, 0x1000, W(d + 2 * hk * dh, d), W(d, d), W(2 * F, d), W(d, F),
+                         0x1000, 0x1000, 4096, Hkv)
+
+
+def test_layer_calls_reject_every_downstream_limit_before_touching_anything(lib):
+    """A layer call that returns an error has enqueued nothing and moved no descriptor: the limits of
+    the later steps (row-kernel width, tokens the score kernel holds, rows the decode attention
+    holds, cache capacity) are checked up front."""
+    from paper_2604_17320_amd import binding
+    ERR_NULL, ERR_INVALID, ERR_SHAPE, ERR_CAPACITY = -1, -2, -3, -4
+    p = binding.ScoreParams(0.25, 0.45, 0.10, 0.20, 10, 90)
+
+    def prefill(L, B, N, Nv, K, cache_len=0, capacity=100000, cache_ptr=0x1000, cacheH=None):
+        cache = binding.KVCache(B, capacity, cacheH or (L.Hkv or L.H), L.dh, cache_len, cache_ptr, cache_ptr,
+                                cache_ptr, cache_ptr)
+        st = binding.State(B, N, 0, Nv, 0x1000, 0x1000, 0x1000, 0x1000)
+        rc = lib.quota_prefill_layer(C.byref(L), C.byref(st), K, C.byref(p), C.byref(cache), None,
+                                     C.c_void_p(0x1000), None)
+        assert (cache.len, st.N, st.Nv) == (cache_len, N, Nv), "descriptors moved by a rejected call"
+        return rc
+
+    ok = _fake_layer(binding)
+    assert prefill(_fake_layer(binding, F=32800), 1, 640, 576, 173) == ERR_SHAPE          # F > 32768
+    assert prefill(_fake_layer(binding, F=11000), 1, 640, 576, 173) == ERR_SHAPE          # F % 32
+    assert prefill(_fake_layer(binding, H=160), 1, 640, 576, 173) == ERR_SHAPE            # d = 20480 > 16384
+    assert prefill(_fake_layer(binding, dh=96), 1, 640, 576, 173) == ERR_SHAPE
+    assert prefill(_fake_layer(binding, Hkv=5), 1, 640, 576, 173) == ERR_SHAPE            # 32 % 5
+    assert prefill(ok, 1, 3200, 3100, 500) == ERR_SHAPE                                   # 3100 scored tokens
+    assert prefill(ok, 1, 640, 576, 173, cache_len=10, capacity=200) == ERR_CAPACITY      # 10 + 237 > 200
+    assert prefill(ok, 1, 640, 576, 173, cache_len=-1) == ERR_INVALID
+    assert prefill(ok, 1, 640, 576, -2) == ERR_INVALID
+    assert prefill(ok, 1, 640, 700, 173) == ERR_INVALID                                   # Nv > N
+    assert prefill(ok, 1, 640, 576, 173, cache_ptr=0) == ERR_NULL
+    assert prefill(_fake_layer(binding, null_weights=True), 1, 640, 576, 173) == ERR_NULL
+    assert prefill(ok, 1, 640, 576, 173, cacheH=8) == ERR_SHAPE                           # cache of another head count
+    bad_w = _fake_layer(binding)
+    bad_w.down = binding.Weights(4096, 11040, 0x1000, 0x1000)                             # K does not match F
+    assert prefill(bad_w, 1, 640, 576, 173) == ERR_SHAPE
+    # a layer outside the candidate set may carry any number of visual tokens (nothing is scored) -- the
+    # only thing left to reject here is the capacity
+    assert prefill(ok, 1, 3200, 3100, -1, capacity=100) == ERR_CAPACITY
+
+    def decode(L, B, cache_len, capacity):
+        cache = binding.KVCache(B, capacity, L.Hkv or L.H, L.dh, cache_len, 0x1000, 0x1000, 0x1000, 0x1000)
+        rc = lib.quota_decode_layer(C.byref(L), C.c_void_p(0x1000), C.c_void_p(0x1000), B, C.byref(cache),
+                                    C.c_void_p(0x1000), None, C.c_void_p(0x1000), None)
+        assert cache.len == cache_len, "cache length moved by a rejected call"
+        return rc
+
+    assert decode(ok, 4, 300, 300) == ERR_CAPACITY
+    assert decode(ok, 4, 8192, 9000) == ERR_SHAPE                                         # 8193 rows to attend over
+    assert decode(_fake_layer(binding, F=32800), 4, 10, 100) == ERR_SHAPE
+    assert decode(ok, 4, -3, 100) == ERR_INVALID
+
+
+def test_gemm_variant_setter(lib):
+    assert lib.quota_set_gemm_variant(5) == -2 and lib.quota_set_gemm_variant(-2) == -2
+    for v in (0, 4, -1):
+        assert lib.quota_set_gemm_variant(v) == 0

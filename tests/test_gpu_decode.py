@@ -12,7 +12,7 @@ import torch
 import oracle
 from paper_2604_17320_amd import workloads as wl
 from test_gpu_ops import _pack4, close_f16, dev, host, unpack4
-from test_gpu_layer import build_layer, rel_rms
+from test_gpu_layer import assert_chain_report, build_layer, chain_report
 
 pytestmark = pytest.mark.gpu
 
@@ -122,7 +122,9 @@ def check_decode(qb, shape, seed, K, steps=2):
         assert close_f16(got["o"], ref["o"])                  # the library's own attention, dumped by the same run
         free = run_decode(qb, L, shape, xn, pn, cache)
         assert close_f16(free["o"], ref["o"])
-        assert rel_rms(free["x1"], ref["x1"]) < 1e-2 and rel_rms(free["x_next"], ref["x_next"]) < 5e-2
+        rep = chain_report(W, free, ref)                      # int4 code flips behind the attention output
+        print("decode free-running report:", rep)
+        assert_chain_report(rep)
         cache = ref["cache"]
 
 

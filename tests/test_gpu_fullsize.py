@@ -155,8 +155,9 @@ def test_layer_batched_serving_shape_sampled_sequence(qb):
     sub = dict(qkv=got["qkv"][rows_all], o=got["o"][rows_all], score=got["score"][b:b + 1],
                keep_idx=got["keep_idx"][b:b + 1], rows=got["rows"][b:b + 1],
                cache_kc=got["cache_kc"][rows_keep], cache_vc=got["cache_vc"][rows_keep],
-               x1=got["x1"][rows_keep], gu=got["gu"][rows_keep], x_next=got["x_next"][rows_keep])
-    check_free_running(ref, sub, one, K)
+               x1=got["x1"][rows_keep], gu=got["gu"][rows_keep], z=got["z"][rows_keep],
+               x_next=got["x_next"][rows_keep], pos_next=got["pos_next"][rows_keep])
+    check_free_running(ref, sub, one, K, W)
     assert got["N"] == n_keep and got["Nv"] == K and got["cache_len"] == n_keep
     # every sequence keeps exactly K visual tokens, ascending, and all text tokens
     for bb in range(16):
@@ -179,4 +180,4 @@ def test_layer_13b_high_resolution_shape(qb):
                                                 cm_intra=ref["cm_intra"]))
     assert_teacher_forced_exact(ref, got, shape, K)
     free = run_gpu(qb, L, shape, x, pos, K)
-    check_free_running(ref, free, shape, K)
+    check_free_running(ref, free, shape, K, W)

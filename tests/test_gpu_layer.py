@@ -138,32 +138,119 @@ def test_layer_small_teacher_forced(qb, name, over, K):
         assert np.allclose(got["cm_intra"], ref["cm_intra"], rtol=2e-5, atol=1e-7)
 
 
-def check_free_running(ref, got, shape, K):
+def close_f32(a, b, rtol=1e-5):
+    """fp32 contract: |a - b| <= rtol * max(|b|, rms(b)), element by element."""
+    a, b = a.astype(np.float64), b.astype(np.float64)
+    rms = np.sqrt((b ** 2).mean()) if b.size else 0.0
+    return bool(np.all(np.abs(a - b) <= rtol * np.maximum(np.abs(b), rms)))
+
+
+# Share of int4 codes that may differ at a quantizer of a free-running chain.  A code flips when the
+# two sides' inputs fall on different sides of a rounding boundary: inputs that differ by one fp16
+# ulp (2^-11 relative) do so with probability ~ |x| / step * 2^-11 per element (a few 1e-3 at most);
+# a row whose absmax element moved re-scales the whole row, which moves more codes of that row.
+# Flips then feed the next quantizer through an exact GEMM and a row normalisation or a product.
+FLIP_BOUND = dict(qa2=2e-3, qa3=2e-3, qa4=5e-3)      # measured: up to 3.3e-4, 1e-5, 8.5e-4
+
+
+def free_running_report(ref, got, shape, K, W):
+    """Where a free-running GPU chain and the oracle part ways, quantizer by quantizer: the int4
+    codes each quantizer WOULD emit for the GPU's tensor (oracle quantizer applied to it -- the GPU
+    quantizers equal it bit for bit on equal inputs) against the oracle's own codes.  Rows are the
+    kept rows common to both sides."""
+    B, N, Nv = shape.B, shape.N, shape.Nv
+    k = min(K, Nv)
+    n_keep = N - Nv + k
+    g_rows, r_rows = got["rows"].reshape(B, n_keep), ref["rows"].reshape(B, n_keep)
+    gi, ri = [], []                                    # positions (in the compacted tensors) of the common rows
+    for b in range(B):
+        common = np.intersect1d(g_rows[b], r_rows[b])
+        gi.append(b * n_keep + np.searchsorted(g_rows[b], common))
+        ri.append(b * n_keep + np.searchsorted(r_rows[b], common))
+    gi, ri = np.concatenate(gi), np.concatenate(ri)
+    flat_g = (np.arange(B)[:, None] * N + g_rows).reshape(-1)[gi]
+    flat_r = (np.arange(B)[:, None] * N + r_rows).reshape(-1)[ri]
+    rep = chain_report(W, dict(o=got["o"][flat_g], x1=got["x1"][gi], gu=got["gu"][gi], z=got["z"][gi], x_next=got["x_next"][gi]),
+                       dict(o=ref["o"][flat_r], x1=ref["x1"][ri], gu=ref["gu"][ri], z=ref["z"][ri], x_next=ref["x_next"][ri]))
+    rep["rows"] = len(gi)
+    return rep, gi, ri
+
+
+def chain_report(W, g, r):
+    """Token-wise rest of the block, GPU tensors `g` against oracle tensors `r` (same rows): share of
+    int4 codes that differ at the three quantizers (in front of O, gate/up, down), and whether every
+    row whose quantized input (codes and scale) agrees is bit-exact behind the GEMM that follows."""
+    rep = {}
+
+    def codes(t):
+        q, s_, _, _ = oracle.quantize_act(t)
+        return q, s_
+
+    def cmp(name, tg, tr):
+        (qg, sg), (qr, sr) = codes(tg), codes(tr)
+        rep[name] = float((qg != qr).mean())
+        return np.all(qg == qr, axis=1) & (sg == sr)
+
+    same2 = cmp("qa2", g["o"], r["o"])
+    same3 = cmp("qa3", oracle.rmsnorm(g["x1"], W.gamma2, W.eps), oracle.rmsnorm(r["x1"], W.gamma2, W.eps))
+    same4 = cmp("qa4", g["z"], r["z"])
+    eq_rows = lambda a, b_: np.all(np.ascontiguousarray(a).view(np.uint16) == np.ascontiguousarray(b_).view(np.uint16), axis=1)
+    x1_eq, gu_eq, xn_eq = eq_rows(g["x1"], r["x1"]), eq_rows(g["gu"], r["gu"]), eq_rows(g["x_next"], r["x_next"])
+    # a GEMM is exact, so a row whose quantized input (codes and scale) and residual agree must agree bit for bit
+    rep["x1_rows_checked"], rep["x1_ok"] = int(same2.sum()), bool(np.all(x1_eq[same2]))
+    rep["gu_rows_checked"], rep["gu_ok"] = int(same3.sum()), bool(np.all(gu_eq[same3]))
+    ok4 = same4 & x1_eq
+    rep["xn_rows_checked"], rep["xn_ok"] = int(ok4.sum()), bool(np.all(xn_eq[ok4]))
+    rep["rel_rms"] = dict(x1=rel_rms(g["x1"], r["x1"]), gu=rel_rms(g["gu"], r["gu"]), x_next=rel_rms(g["x_next"], r["x_next"]))
+    return rep
+
+
+def assert_chain_report(rep):
+    for q in ("qa2", "qa3", "qa4"):
+        assert rep[q] <= FLIP_BOUND[q], (q, rep[q])
+    assert rep["x1_ok"] and rep["gu_ok"] and rep["xn_ok"], rep
+    assert rep["rel_rms"]["x1"] < 1e-2 and rep["rel_rms"]["gu"] < 5e-2 and rep["rel_rms"]["x_next"] < 5e-2
+
+
+def check_free_running(ref, got, shape, K, W):
+    """Free-running chain (the GPU consumes its own floats) against the oracle.  fp16 tensors in front
+    of the first re-quantization within 1e-2, scores within 1e-5 relative; kept sets equal except
+    for tokens whose oracle score lies within that score tolerance of the cut (each printed); K/V
+    codes of the common rows bit-exact.  Behind the attention output every tensor sits behind an
+    int4 quantizer, where a one-ulp input difference can move a value by a whole quantization step:
+    an element-wise fp16 bound cannot hold there (an earlier version of this test asserted it at the
+    7B shape and failed on x1 and gu), so what is asserted instead is (a) the share of flipped int4
+    codes at each quantizer stays under a stated bound and (b) every row whose quantized input did
+    not flip is bit-exact behind the following GEMM.  The relative rms is reported as a secondary
+    figure."""
     B, Nv = shape.B, shape.Nv
     k = min(K, Nv)
     n_keep = shape.N - Nv + k
     assert np.array_equal(np.ascontiguousarray(got["qkv"]).view(np.uint16), ref["qkv"].view(np.uint16))
     assert close_f16(got["o"], ref["o"])
-    assert np.allclose(got["score"], ref["score"], rtol=1e-5, atol=2e-5)
-    # index sets: equal, except swaps among tokens whose oracle scores are within the fp tolerance of the cut
+    if Nv:
+        assert close_f32(got["score"], ref["score"]), np.abs(got["score"] - ref["score"]).max()
+    # index sets: equal, except swaps among tokens whose oracle scores are within the score tolerance of the cut
     for b in range(B):
         a, r = set(got["keep_idx"][b, :k].tolist()), set(ref["keep_idx"][b].tolist())
         if a != r:
-            sc = ref["score"][b]
+            sc = ref["score"][b].astype(np.float64)
             cut = np.sort(sc)[::-1][k - 1]
-            for i in a ^ r:
-                assert abs(sc[i] - cut) <= 1e-4, (b, i, sc[i], cut)
-    if all(set(got["keep_idx"][b, :k].tolist()) == set(ref["keep_idx"][b].tolist()) for b in range(B)):
-        assert np.array_equal(got["rows"], ref["rows"])
-        # K/V codes come from the bit-exact qkv: no float chain before them
-        assert np.array_equal(got["cache_kc"], ref["cache_kc"]) and np.array_equal(got["cache_vc"], ref["cache_vc"])
-        # Past the attention output every tensor sits behind an int4 quantizer: a one-ulp
-        # difference in o can flip a code, i.e. move an input by a whole quantization step, so
-        # the elementwise fp16 bound no longer applies to a free-running chain (the teacher-forced
-        # test is the exactness proof).  What must hold is statistical closeness.
-        assert rel_rms(got["x1"], ref["x1"]) < 1e-2
-        assert rel_rms(got["gu"], ref["gu"]) < 5e-2
-        assert rel_rms(got["x_next"][: B * n_keep], ref["x_next"]) < 5e-2
+            tol = 2e-5 * max(abs(cut), float(np.sqrt((sc ** 2).mean())))      # 1e-5 relative on either side
+            for i in sorted(a ^ r):
+                print(f"kept-set exception: sequence {b} token {i} score {sc[i]:.9g} cut {cut:.9g} gap {abs(sc[i] - cut):.3g}")
+                assert abs(sc[i] - cut) <= tol, (b, i, sc[i], cut)
+    if n_keep == 0:
+        return None
+    rep, gi, ri = free_running_report(ref, got, shape, K, W)
+    print("free-running report:", rep)
+    assert rep["rows"] >= B * (n_keep - 2 * 4)           # at most a few tokens swapped at the cut
+    # K/V codes come from the bit-exact qkv: no float chain before them
+    assert np.array_equal(got["cache_kc"][gi], ref["cache_kc"][ri]) and np.array_equal(got["cache_vc"][gi], ref["cache_vc"][ri])
+    assert np.array_equal(got["pos_next"][gi], ref["pos_next"][ri])
+    assert_chain_report(rep)
+    assert rep["x1_rows_checked"] > 0
+    return rep
 
 
 def rel_rms(a, b):
@@ -179,7 +266,7 @@ def test_layer_small_free_running(qb):
     for K in (19, 20):
         ref = oracle.prefill_layer(W, x, pos, 1, shape.N, 0, shape.Nv, K, cos, sin)
         got = run_gpu(qb, L, shape, x, pos, K)
-        check_free_running(ref, got, shape, K)
+        check_free_running(ref, got, shape, K, W)
 
 
 def test_layer_7b_shape_full_size(qb):
@@ -195,7 +282,7 @@ def test_layer_7b_shape_full_size(qb):
                                                 cm_intra=ref["cm_intra"]))
     assert_teacher_forced_exact(ref, got, shape, K)
     free = run_gpu(qb, L, shape, x, pos, K)
-    check_free_running(ref, free, shape, K)
+    check_free_running(ref, free, shape, K, W)
 
 
 def test_layer_errors(qb):
@@ -243,10 +330,10 @@ def test_layer_without_taps_equals_layer_with_taps(qb):
 
 
 @pytest.mark.parametrize("tile", [1, 2, 3, 4])
-def test_layer_every_tile_with_fused_qkv_epilogue(qb, tile, monkeypatch):
+def test_layer_every_tile_with_fused_qkv_epilogue(qb, tile, pinned_gemm):
     """The QKV projection with its fused RoPE / KV-quantizer epilogue on each tile that carries it
     (and every other GEMM of the layer on the same tile), teacher-forced bit-exact."""
-    monkeypatch.setenv("QUOTA_GEMM_TILE", str(tile))
+    pinned_gemm(tile)
     base = wl.CONFIGS[0]
     shape = wl.Shape("tile", d=base.d, H=base.H, F=base.F, layers=1, B=2, Nv=base.Nv, Nt=21,
                      n_outlier=base.n_outlier, vis_begin=0)

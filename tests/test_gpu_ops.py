@@ -84,7 +84,7 @@ def _act(M, d, seed, scale=1.0):
     return x.astype(np.float16)
 
 
-@pytest.mark.parametrize("M,d", [(80, 512), (37, 1376), (640, 4096), (5, 11008), (3, 16384), (1, 8)])
+@pytest.mark.parametrize("M,d", [(80, 512), (37, 1376), (640, 4096), (5, 11008), (3, 16384), (1, 8), (5, 18944), (2, 32768)])
 def test_quantize_act_bit_exact(qb, M, d):
     x = _act(M, d, 11)
     if M > 2:
@@ -115,14 +115,14 @@ def test_quantize_act_errors(qb):
     s = torch.zeros(4, dtype=torch.float32, device="cuda")
     for args, code in [((x, 4, 60, 64, q, s), qb.ERR_SHAPE), ((x, 4, 64, 32, q, s), qb.ERR_SHAPE),
                        ((x, -1, 64, 64, q, s), qb.ERR_INVALID_ARG), ((None, 4, 64, 64, q, s), qb.ERR_NULL),
-                       ((x, 4, 16392, 16392, q, s), qb.ERR_SHAPE)]:
+                       ((x, 4, 32776, 32776, q, s), qb.ERR_SHAPE)]:
         with pytest.raises(qb.QuotaError) as e:
             qb.quota_quantize_act(*args)
         assert e.value.code == code
     qb.quota_quantize_act(x, 0, 64, 64, q, s)          # empty input is fine
 
 
-@pytest.mark.parametrize("M,d", [(80, 512), (33, 4096), (6, 5120)])
+@pytest.mark.parametrize("M,d", [(80, 512), (33, 4096), (6, 5120), (3, 18944)])
 def test_rmsnorm_quantize_act(qb, M, d):
     x = _act(M, d, 12, 1.7)
     gamma = wl.rng(12, "gamma", d).uniform(0.5, 1.5, d).astype(np.float32)
@@ -142,7 +142,7 @@ def test_rmsnorm_quantize_act(qb, M, d):
     assert torch.equal(qp2, qp) and torch.equal(sc2, sc)
 
 
-@pytest.mark.parametrize("M,F", [(35, 1376), (9, 11008)])
+@pytest.mark.parametrize("M,F", [(35, 1376), (9, 11008), (7, 18944), (2, 32768)])
 def test_silu_mul_quantize_act(qb, M, F):
     gu = (_act(M, 2 * F, 13, 1.5))
     z = oracle.silu_mul(gu, F)
@@ -199,11 +199,11 @@ def test_w4a4_gemm_bit_exact(qb, M, N, K):
 
 
 @pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
-def test_w4a4_gemm_every_tile_bit_exact(qb, tile, monkeypatch):
-    """Each of the five tile instantiations, pinned through the environment, on shapes with ragged
+def test_w4a4_gemm_every_tile_bit_exact(qb, tile, pinned_gemm):
+    """Each of the five tile instantiations, pinned with quota_set_gemm_variant, on shapes with ragged
     rows, a ragged last group and several column tiles."""
     from paper_2604_17320_amd.model import PackedLinear
-    monkeypatch.setenv("QUOTA_GEMM_TILE", str(tile))
+    pinned_gemm(tile)
     for M, N, K in [(150, 1024, 1376), (70, 512, 4096)]:
         qa, sa, qw, sw, res = _gemm_case(M, N, K, 23)
         y_ref = oracle.w4a4_gemm(qa, sa, qw, sw, residual=res)

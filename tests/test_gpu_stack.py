@@ -125,3 +125,41 @@ def test_stack_hip_graph_replays_equal_eager(qb):
             assert torch.equal(c.k_codes[:, :n], w[:, :n]), rep
         stack.run(x, pos)                 # eager work between replays
         torch.cuda.synchronize()
+
+
+def test_stack_prunes_at_candidate_layers_only(qb):
+    """The recipe prunes at the candidate layers only: layers marked KEEP_ALL run no cue pass, no
+    score and no top-k and keep every token.  For the oracle such a layer is one whose budget keeps
+    everything (its scores then change nothing).  Six layers, candidates 2..3; teacher-forced, so the
+    hidden state, positions and every layer's 4-bit cache must be bit-exact."""
+    from paper_2604_17320_amd.model import make_taps
+    budgets = [qb.KEEP_ALL, qb.KEEP_ALL, 30, 12, qb.KEEP_ALL, qb.KEEP_ALL]
+    oracle_budgets = [10 ** 6, 10 ** 6, 30, 12, 10 ** 6, 10 ** 6]
+    B = 2
+    shape, Ws, stack, cos, sin = small_stack(6, B, budgets)
+    x, pos = wl.hidden_state(shape, 9), wl.positions(shape)
+    ref = oracle_prefill(shape, Ws, oracle_budgets, x, pos, cos, sin)
+    keep, taps = [], []
+    score_taps = []
+    for l, o in enumerate(ref):
+        t = {k: dev(o[k]) for k in ("o", "z", "cm_inter", "cm_intra")}
+        sc = torch.full((B, o["score"].shape[1]), -7.0, dtype=torch.float32, device="cuda")
+        keep.append(t)
+        score_taps.append(sc)
+        taps.append(make_taps(inject_o=t["o"], inject_z=t["z"], inject_cm_inter=t["cm_inter"],
+                              inject_cm_intra=t["cm_intra"], score=sc))
+    xo, po, N, Nv = stack.run(dev(x), dev(pos), taps)
+    last = ref[-1]
+    assert (N, Nv) == (last["n_keep"], last["Nv_next"]) == (12 + shape.Nt, 12)
+    assert eq16(host(xo), last["x_next"]) and np.array_equal(host(po), last["pos_next"])
+    for l, o in enumerate(ref):
+        c, n = stack.caches[l], o["n_keep"]
+        assert c.len == n
+        assert np.array_equal(unpack4(host(c.k_codes)[:, :n]).reshape(B * n, -1), o["cache_kc"])
+        assert eq16(host(c.v_scales)[:, :n].reshape(B * n, -1), o["cache_vs"])
+        # a layer outside the candidate set produced no score at all; a candidate layer produced the oracle's
+        got_sc = host(score_taps[l])
+        if budgets[l] == qb.KEEP_ALL:
+            assert np.all(got_sc == -7.0)
+        else:
+            assert np.array_equal(got_sc, o["score"])

@@ -640,3 +640,117 @@ def test_gqa_layer_cache_width_and_decode_consistency():
     for key in ("q", "o", "x1", "x_next"):
         assert np.array_equal(dec[key], full[key][last]), key
     assert np.array_equal(dec["kc"], full["kc"][last])
+
+
+# ------------------------------------------------ block wiring of the layer composite
+def _llama_block_fp64(x, Wqkv, Wo, Wgu, Wd, g1, g2, eps, H, dh, pos, mistake=None):
+    """A LLaMA-style decoder block in plain fp64 numpy, written without the oracle: RMSNorm -> q|k|v
+    projection -> rotate-half RoPE on q and k -> causal softmax attention -> output projection +
+    residual -> RMSNorm -> gate|up projection -> SiLU(gate) * up -> down projection + residual.
+    No quantizer anywhere.  `mistake` plants one wiring error (negative controls)."""
+    N, d = x.shape
+    F = Wd.shape[1]
+    norm = lambda t, g: t / np.sqrt((t * t).mean(axis=1, keepdims=True) + eps) * g
+    h = norm(x, g1)
+    qkv = (x if mistake == "no_norm_before_qkv" else h) @ Wqkv.T
+    q, k, v = qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:]
+    if mistake == "k_v_swapped":
+        k, v = v, k
+    inv = 1.0e4 ** (-np.arange(0, dh, 2) / dh)
+    ang = pos[:, None] * inv[None, :]
+    cos, sin = np.cos(ang), np.sin(ang)
+
+    def rope(t):
+        t = t.reshape(N, H, dh)
+        a, b = t[..., :dh // 2], t[..., dh // 2:]
+        return np.concatenate([a * cos[:, None] - b * sin[:, None], b * cos[:, None] + a * sin[:, None]], axis=-1).reshape(N, d)
+
+    q = rope(q)
+    if mistake != "k_not_rotated":
+        k = rope(k)
+    if mistake == "v_rotated":
+        v = rope(v)
+    o = np.zeros((N, d))
+    for hd in range(H):
+        sl = slice(hd * dh, (hd + 1) * dh)
+        s = q[:, sl] @ k[:, sl].T / np.sqrt(dh)
+        s = np.where(np.tril(np.ones((N, N), bool)), s, -np.inf)
+        p = np.exp(s - s.max(axis=1, keepdims=True))
+        o[:, sl] = (p / p.sum(axis=1, keepdims=True)) @ v[:, sl]
+    x1 = (h if mistake == "residual_is_normed_input" else x) + o @ Wo.T
+    h2 = norm(x1, g2)
+    gu = h2 @ Wgu.T
+    g, u = (gu[:, F:], gu[:, :F]) if mistake == "gate_up_swapped" else (gu[:, :F], gu[:, F:])
+    z = g / (1.0 + np.exp(-g)) * u
+    xn = (x if mistake == "second_residual_is_block_input" else x1) + z @ Wd.T
+    return dict(attn_branch=x1 - x, ffn_branch=xn - x1, x1=x1, x_next=xn, q=q, k=k, v=v, o=o, gu=gu, z=z)
+
+
+def test_layer_wiring_against_an_independent_fp64_block():
+    """Pins WHICH tensor feeds which step in oracle/layer.py (residual sources, RMSNorm output into
+    the projections, q|k|v and gate|up row order, what is rotated).  The reference is the plain fp64
+    block above run on the dequantized W4 weights; the oracle adds int4 activation and 4-bit K/V
+    noise (about 12 % of a GEMM output's rms each), so the two branch outputs must agree in
+    direction (cosine > 0.85) and size (within 25 %), and so must the tensors between the steps (rotated
+    q, the 4-bit K and V, attention output, gate|up, SwiGLU product); every planted wiring mistake drops
+    the tensor or branch it touches below 0.75 or out of the size band.  Larger weights than the workload's make both branches
+    comparable to the residual stream so that no term hides behind it."""
+    d, H, dh, F, Nv, Nt = 256, 4, 64, 512, 40, 8
+    N = Nv + Nt
+    r = R(77)
+    # rows of very different size and uneven gains: skipping a normalisation or using its output as the
+    # residual changes sizes, not only directions
+    x = (r.standard_normal((N, d)) * r.uniform(0.5, 4.0, (N, 1))).astype(np.float16)
+    pos = (300 + 7 * np.arange(N)).astype(np.int32)       # non-contiguous position ids, as after pruning
+    g1 = r.uniform(0.3, 2.0, d).astype(np.float32)
+    g2 = r.uniform(0.3, 2.0, d).astype(np.float32)
+    fw = dict(qkv=r.standard_normal((3 * d, d)) * 0.08, o=r.standard_normal((d, d)) * 0.08,
+              gu=r.standard_normal((2 * F, d)) * 0.08, down=r.standard_normal((d, F)) * 0.08)
+    q = {k_: oracle.quantize_weights(v_.astype(np.float32)) for k_, v_ in fw.items()}
+    deq = {k_: c.astype(np.float64) * np.repeat(s_.astype(np.float64), 128, axis=1)[:, :c.shape[1]] for k_, (c, s_) in q.items()}
+    W = oracle.LayerWeights(qkv=q["qkv"], o=q["o"], gu=q["gu"], down=q["down"], gamma1=g1, gamma2=g2, eps=1e-5,
+                            H=H, dh=dh, F=F)
+    cos, sin = wl.rope_tables(dh, int(pos.max()) + 1)
+    out = oracle.prefill_layer(W, x, pos, 1, N, 0, Nv, Nv, cos, sin)           # K = Nv: nothing pruned
+    xf = x.astype(np.float64)
+    got = dict(attn_branch=out["x1"].astype(np.float64) - xf, ffn_branch=out["x_next"].astype(np.float64) - out["x1"].astype(np.float64))
+    for name, key in dict(q="q", k="khat", v="vhat", o="o", gu="gu", z="z").items():      # tensors between the steps
+        got[name] = out[key].astype(np.float64)
+
+    def agree(a, b):
+        a, b = a.ravel(), b.ravel()
+        return float(a @ b / np.sqrt((a @ a) * (b @ b))), float(np.sqrt((a @ a) / (b @ b)))
+
+    ref = _llama_block_fp64(xf, deq["qkv"], deq["o"], deq["gu"], deq["down"], g1, g2, 1e-5, H, dh, pos.astype(np.float64))
+    for branch in ("q", "k", "v", "o", "gu", "z", "attn_branch", "ffn_branch"):
+        c, ratio = agree(got[branch], ref[branch])
+        print(branch, round(c, 3), round(ratio, 3))
+        assert c > 0.85 and 0.75 < ratio < 1.25, (branch, c, ratio)
+    for branch in ("attn_branch", "ffn_branch"):
+        # the branch is not hidden behind the residual stream
+        assert np.sqrt((ref[branch] ** 2).mean()) > 0.2 * np.sqrt((xf ** 2).mean())
+    # negative controls: each planted mistake must break the agreement of the branch it touches
+    touched = dict(no_norm_before_qkv="q", k_v_swapped="k", k_not_rotated="k", v_rotated="v",
+                   residual_is_normed_input="attn_branch", gate_up_swapped="z")
+    for mistake, branch in touched.items():
+        bad = _llama_block_fp64(xf, deq["qkv"], deq["o"], deq["gu"], deq["down"], g1, g2, 1e-5, H, dh,
+                                pos.astype(np.float64), mistake=mistake)
+        c, ratio = agree(got[branch], bad[branch])
+        print(mistake, round(c, 3), round(ratio, 3))
+        assert c < 0.75 or not 0.75 < ratio < 1.25, (mistake, c, ratio)
+
+    # The two residual sources, exactly: what a projection adds is the fp64 product of ITS dequantized
+    # operands, so (block output - that product) must be the residual tensor up to the fp16 rounding
+    # of the sum -- and must not be any other tensor of the block.
+    def deq_act(qa, sa):
+        return qa.astype(np.float64) * sa.astype(np.float64)[:, None]
+
+    add_o = deq_act(out["qa2"], out["sa2"]) @ deq["o"].T
+    add_d = deq_act(out["qa4"], out["sa4"]) @ deq["down"].T
+    x1f, xnf = out["x1"].astype(np.float64), out["x_next"].astype(np.float64)
+    tol = lambda t: 2.0 ** -10 * np.maximum(np.abs(t), 1.0)
+    assert np.all(np.abs((x1f - add_o) - xf) <= tol(x1f))                    # first residual: the block input
+    assert np.all(np.abs((xnf - add_d) - x1f) <= tol(xnf))                   # second residual: x1
+    assert not np.all(np.abs((x1f - add_o) - out["h1"].astype(np.float64)) <= tol(x1f))
+    assert not np.all(np.abs((xnf - add_d) - xf) <= tol(xnf))
+    assert not np.all(np.abs((xnf - add_d) - out["h2"].astype(np.float64)) <= tol(xnf))
