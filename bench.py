@@ -22,7 +22,11 @@ PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA, TOP/s
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, GB/s
 
 
-def build_stack(shape, seed, budgets, keep_plain_layers=()):
+def build_stack(shape, seed, budgets, with_oracle=False):
+    """The layer stack on the GPU (weights drawn by the seeded device generator, quantized and packed
+    by the library).  with_oracle: also the same fp32 weights quantized by the ORACLE's own weight
+    quantizer, as host arrays for the CPU legs (nothing the oracle reads comes from the HIP path)."""
+    import numpy as np
     import torch
     from paper_2604_17320_amd import workloads as wl
     from paper_2604_17320_amd.model import PackedLinear, PrefillLayer, PrefillStack
@@ -30,20 +34,22 @@ def build_stack(shape, seed, budgets, keep_plain_layers=()):
     cos, sin = wl.rope_tables(shape.dh, shape.N)
     cosT, sinT = torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda()
     gamma = torch.ones(d, dtype=torch.float32, device="cuda")
-    layers = []
+    layers, oracle_layers = [], []
     for l in range(shape.layers):
-        g = torch.Generator(device="cuda")
-        g.manual_seed(seed * 1000 + l)
-        lin = {}
-        for name, (n, k) in dict(qkv=(3 * d, d), o=(d, d), gu=(2 * F, d), down=(d, F)).items():
-            w = torch.randn((n, k), generator=g, device="cuda", dtype=torch.float32) * 0.02
-            lin[name] = PackedLinear.from_fp32(w, keep_plain=l in keep_plain_layers)
-            del w
+        fw = wl.fp_weights_device(shape, seed, l)
+        lin = {name: PackedLinear.from_fp32(w) for name, w in fw.items()}
+        if with_oracle:
+            import oracle
+            q = {name: oracle.quantize_weights(w.cpu().numpy()) for name, w in fw.items()}
+            g = np.ones(d, np.float32)
+            oracle_layers.append(oracle.LayerWeights(qkv=q["qkv"], o=q["o"], gu=q["gu"], down=q["down"], gamma1=g,
+                                                     gamma2=g, eps=1e-5, H=shape.H, dh=shape.dh, F=F))
+        del fw
         layers.append(PrefillLayer(shape.H, shape.dh, F, lin["qkv"], lin["o"], lin["gu"], lin["down"],
                                    gamma, gamma, 1e-5, cosT, sinT))
     torch.cuda.synchronize()
     stack = PrefillStack(layers, shape.B, shape.N, shape.vis_begin, shape.Nv, budgets)
-    return stack, (cos, sin)
+    return stack, (cos, sin), oracle_layers
 
 
 def measured_traffic(kernel):
@@ -179,41 +185,97 @@ def serving_decode(shape, stack, budgets, seed, steps=16):
                 frac_hbm_peak=round((wbytes + kv_bytes) / (ms * 1e-3) / (PEAK_HBM_GBS * 1e9), 4))
 
 
-def cpu_baseline(shape, stack, budgets, rope, sample_layers, seed):
-    """The oracle, as it stands, on a bounded sample: a few layers of the stack, each fed a
-    synthetic hidden state with the row count that layer sees in the real run."""
-    import numpy as np
+def cpu_baseline(shape, oracle_layers, budgets, rope, x0, pos0):
+    """The oracle, as it stands, on the whole workload: every layer in full, each fed what the layer
+    before it produced (its own compacted hidden state and positions).  Only the oracle's layer calls
+    are timed.  Returns the JSON record and, per layer, what the check leg compares against."""
     import oracle
-    from paper_2604_17320_amd import workloads as wl
     cos, sin = rope
-    rows_in = []
-    n, nv = shape.N, shape.Nv
-    for K in budgets:
-        rows_in.append((n, nv))
-        k = nv if K < 0 else min(K, nv)
-        n, nv = n - nv + k, k
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    t_sum, r_sum = 0.0, 0
-    for l in sample_layers:
-        L = stack.layers[l]
-        W = oracle.LayerWeights(
-            **{name: (getattr(L, name).codes.cpu().numpy(), getattr(L, name).plain_scales.cpu().numpy())
-               for name in ("qkv", "o", "gu", "down")},
-            gamma1=np.ones(shape.d, np.float32), gamma2=np.ones(shape.d, np.float32), eps=1e-5,
-            H=shape.H, dh=shape.dh, F=shape.F)
-        n, nv = rows_in[l]
-        sh = wl.Shape("sample", shape.d, shape.H, shape.F, 1, shape.B, nv, n - nv, shape.n_outlier)
-        x = wl.hidden_state(sh, seed + l)
-        pos = wl.positions(sh)
+    x, pos, N, Nv = x0, pos0, shape.N, shape.Nv
+    refs, t_sum, rows = [], 0.0, 0
+    for W, K in zip(oracle_layers, budgets):
+        Ko = 10 ** 9 if K < 0 else K
         t0 = time.perf_counter()
-        oracle.prefill_layer(W, x, pos, shape.B, n, 0, nv, budgets[l], cos, sin, prune_mid=True)
+        o = oracle.prefill_layer(W, x, pos, shape.B, N, shape.vis_begin, Nv, Ko, cos, sin, prune_mid=True)
         t_sum += time.perf_counter() - t0
-        r_sum += shape.B * n
-    rows_total = sum(shape.B * n for n, _ in rows_in)
-    est = t_sum * rows_total / r_sum                 # seconds for the whole stack, by row count
-    return dict(value=shape.B * shape.N / est, unit="tokens/s", cores=threads, kind="oracle",
-                sample=f"layers {list(sample_layers)} of {shape.layers} run in full ({t_sum:.2f} s, {r_sum} "
-                       f"token-rows), scaled by token-rows to all layers ({rows_total} rows)")
+        rows += shape.B * N
+        refs.append(dict(x_in=x, pos_in=pos, N=N, Nv=Nv, K=K, keep_idx=o["keep_idx"], score=o["score"], rows=o["rows"],
+                         n_keep=o["n_keep"], cache_kc=o["cache_kc"], cache_vc=o["cache_vc"], x_next=o["x_next"],
+                         pos_next=o["pos_next"]))
+        x, pos, N, Nv = o["x_next"], o["pos_next"], o["n_keep"], o["Nv_next"]
+    rec = dict(value=shape.B * shape.N / t_sum, unit="tokens/s", cores=threads, kind="oracle",
+               sample=f"all {len(oracle_layers)} layers run in full on the propagated inputs ({t_sum:.2f} s, {rows} "
+                      f"token-rows); weight quantization and set-up not timed")
+    return rec, refs
+
+
+def check_against_oracle(shape, stack, refs, sample_layers, gpu_final):
+    """Untimed parity leg on the benchmark's own weights.  For each sampled layer the GPU layer is run
+    (free-running, nothing injected) on the ORACLE's input of that layer and compared with the
+    oracle's output: kept index sets (equal, or differing only in tokens whose oracle score is within
+    2e-5 relative of the cut), the 4-bit K/V codes of the kept rows common to both (bit-exact), the
+    output hidden state (relative rms).  Plus how far the GPU's own free-running 32-layer chain ends
+    from the oracle's chain (kept original positions in common)."""
+    import numpy as np
+    import torch
+    from paper_2604_17320_amd import binding as qb
+    from paper_2604_17320_amd.model import KVCache4
+    B, d = shape.B, shape.d
+    out, ok = [], True
+    for l in sample_layers:
+        r = refs[l]
+        N, Nv, K, n_keep = r["N"], r["Nv"], r["K"], r["n_keep"]
+        k = Nv if K < 0 else min(K, Nv)
+        L = stack.layers[l]
+        cache = KVCache4(B, n_keep, L.Hkv, L.dh)
+        xd, pd = torch.from_numpy(r["x_in"]).cuda(), torch.from_numpy(r["pos_in"]).cuda()
+        x_out = torch.zeros((B * n_keep, d), dtype=torch.float16, device="cuda")
+        pos_out = torch.zeros((B * n_keep,), dtype=torch.int32, device="cuda")
+        keep_idx = torch.zeros((B, max(k, 1)), dtype=torch.int32, device="cuda")
+        rows = torch.zeros((B, n_keep), dtype=torch.int32, device="cuda")
+        taps = qb.Taps()
+        taps.keep_idx, taps.rows = keep_idx.data_ptr(), rows.data_ptr()
+        st = qb.State(B, N, shape.vis_begin, Nv, xd.data_ptr(), pd.data_ptr(), x_out.data_ptr(), pos_out.data_ptr())
+        qb.quota_prefill_layer(L.desc, st, K, stack.params, cache.desc, taps, stack.ws)
+        torch.cuda.synchronize()
+        gk, grow = keep_idx.cpu().numpy()[:, :k], rows.cpu().numpy()
+        exceptions, worst_gap = 0, 0.0
+        for b in range(B):
+            a, rr = set(gk[b].tolist()), set(r["keep_idx"][b].tolist())
+            if a != rr:
+                sc = r["score"][b].astype(np.float64)
+                cut = np.sort(sc)[::-1][k - 1]
+                tol = 2e-5 * max(abs(cut), float(np.sqrt((sc ** 2).mean())))
+                for i in a ^ rr:
+                    exceptions += 1
+                    worst_gap = max(worst_gap, abs(sc[i] - cut))
+                    ok = ok and abs(sc[i] - cut) <= tol
+        # K/V codes of the rows kept by both sides
+        kv_equal, common_rows = True, 0
+        gkc = cache.k_codes.cpu().numpy().reshape(B, n_keep, -1)
+        gvc = cache.v_codes.cpu().numpy().reshape(B, n_keep, -1)
+        rkc, rvc = r["cache_kc"].reshape(B, n_keep, -1), r["cache_vc"].reshape(B, n_keep, -1)
+        pack = lambda c: ((c[..., 0::2] & 0xF) | ((c[..., 1::2] & 0xF) << 4)).astype(np.uint8)
+        rel = []
+        gx = x_out.cpu().numpy().reshape(B, n_keep, d).astype(np.float64)
+        rx = r["x_next"].reshape(B, n_keep, d).astype(np.float64)
+        for b in range(B):
+            common = np.intersect1d(grow[b], r["rows"][b])
+            gi, ri = np.searchsorted(grow[b], common), np.searchsorted(r["rows"][b], common)
+            common_rows += len(common)
+            kv_equal = kv_equal and np.array_equal(gkc[b, gi], pack(rkc[b, ri])) and np.array_equal(gvc[b, gi], pack(rvc[b, ri]))
+            rel.append(((gx[b, gi] - rx[b, ri]) ** 2).sum() / max((rx[b, ri] ** 2).sum(), 1e-30))
+        ok = ok and kv_equal
+        out.append(dict(layer=l, rows_in=N, kept=n_keep, kept_set_exceptions=exceptions,
+                        worst_exception_gap=worst_gap, common_rows=common_rows, kv_codes_bit_exact=bool(kv_equal),
+                        x_next_rel_rms=round(float(np.sqrt(np.mean(rel))), 5)))
+    gx, gp, gN, gNv = gpu_final
+    last = refs[-1]
+    gp_h, rp = gp.cpu().numpy().reshape(B, gN), last["pos_next"].reshape(B, -1)
+    overlap = float(np.mean([len(np.intersect1d(gp_h[b], rp[b])) / rp.shape[1] for b in range(B)]))
+    return dict(ok=bool(ok), layers=out, free_running_chain=dict(
+        tokens_left=gN, oracle_tokens_left=int(rp.shape[1]), kept_positions_in_common=round(overlap, 4)))
 
 
 def main():
@@ -249,9 +311,10 @@ def main():
     shape = {"c1": wl.CONFIGS[0], "c2": wl.CONFIGS[1], "c3": wl.CONFIGS[2]}[args.config]
     budgets = wl.schedule_for(shape)
     sample_layers = sorted({0, min(2, shape.layers - 1), shape.layers // 2, shape.layers - 1})
-    stack, rope = build_stack(shape, args.seed, budgets, keep_plain_layers=() if args.no_cpu else sample_layers)
-    x0 = torch.from_numpy(wl.hidden_state(shape, args.seed)).cuda()
-    pos0 = torch.from_numpy(wl.positions(shape)).cuda()
+    stack, rope, oracle_layers = build_stack(shape, args.seed, budgets, with_oracle=not args.no_cpu)
+    x0_host, pos0_host = wl.hidden_state(shape, args.seed), wl.positions(shape)
+    x0 = torch.from_numpy(x0_host).cuda()
+    pos0 = torch.from_numpy(pos0_host).cuda()
 
     def step():
         return stack.run(x0, pos0)
@@ -359,8 +422,14 @@ def main():
         if args.config == "c3":
             out["serving_decode"] = serving_decode(shape, stack, budgets, args.seed)
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(shape, stack, budgets, rope, sample_layers, args.seed)
+        out["cpu_baseline"], refs = cpu_baseline(shape, oracle_layers, budgets, rope, x0_host, pos0_host)
+        final = step()
+        torch.cuda.synchronize()
+        out["check"] = check_against_oracle(shape, stack, refs, sample_layers, final)
     print(json.dumps(out))
+    if not args.no_cpu and not out["check"]["ok"]:
+        print("bench.py: the untimed parity check against the oracle FAILED (see \"check\")", file=sys.stderr)
+        sys.exit(3)
 
 
 if __name__ == "__main__":

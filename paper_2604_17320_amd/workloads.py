@@ -114,3 +114,18 @@ def schedule_for(shape: Shape):
     if shape.name.startswith("c5"):
         return keep_schedule(shape.layers, shape.Nv, Fraction(1, 5), Fraction(1, 20))
     return keep_schedule(shape.layers, shape.Nv, Fraction(3, 10), Fraction(1, 10))
+
+
+def fp_weights_device(shape: Shape, seed: int = 0, layer: int = 0, device: str = "cuda") -> dict:
+    """The same four fp32 N(0, 0.02) matrices drawn by torch's seeded DEVICE generator: what the
+    benchmark and the full-depth tests use, where 32-40 layers of 200-300 M weights each are too slow
+    to draw on the host.  Returns torch tensors on ``device``; ``.cpu().numpy()`` gives the oracle the
+    same values."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed * 1000 + layer)
+    d, F = shape.d, shape.F
+    out = {}
+    for name, (n, k) in dict(qkv=(3 * d, d), o=(d, d), gu=(2 * F, d), down=(d, F)).items():
+        out[name] = torch.randn((n, k), generator=g, device=device, dtype=torch.float32) * 0.02
+    return out
