@@ -11,6 +11,14 @@ event-timed averages.  `traffic` turns two `--pmc` passes (FETCH_SIZE, then WRIT
 dispatch) into HBM bytes per launch for each library kernel; both counters are scaled by what
 they read for the plain elementwise copy of known size that bench.py ran in the same process
 (`--calibration-copy-mib`), and the JSON goes to stdout.
+
+    python -m paper_2604_17320_amd.profile_summary mfma <sq_counter_collection.csv> [bench.json]
+
+`mfma` condenses one `--pmc` pass of SQ counters (SQ_INSTS_MFMA SQ_INSTS_VALU
+SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_ACTIVE_INST_VALU SQ_WAVE_CYCLES SQ_WAIT_INST_ANY
+SQ_WAVES) into one line per GEMM kernel class: MFMA instructions issued per launch and what they
+amount to against the int8 dense peak over the dispatch's own duration, vector instructions per
+MFMA, and the busy / wait shares the counters give.
 """
 import collections
 import csv
@@ -123,9 +131,45 @@ def traffic(fetch_csv, write_csv, copy_mib, bench_path=None):
     print(json.dumps(out, indent=1))
 
 
+def mfma(csv_path, bench_path=None):
+    bench = load_bench(bench_path)
+    per = collections.defaultdict(lambda: collections.defaultdict(list))     # class -> counter -> values
+    dur = collections.defaultdict(dict)                                      # class -> dispatch id -> ns
+    for r in csv.DictReader(open(csv_path)):
+        cls = classify(r["Kernel_Name"])
+        if cls is None or not cls.startswith("w4a4_gemm"):
+            continue
+        per[cls][r["Counter_Name"]].append(float(r["Counter_Value"]))
+        dur[cls][r["Dispatch_Id"]] = float(r["End_Timestamp"]) - float(r["Start_Timestamp"])
+    mean = lambda v: sum(v) / len(v) if v else float("nan")
+    print("per launch, mean over the dispatches of each GEMM kernel class (durations are those of the counter run, "
+          "which serialises kernels and is slower than a plain run)")
+    print(f"{'kernel':24s} {'launches':>8s} {'us':>7s} {'MFMA inst':>10s} {'issued TOP/s':>12s} {'of int8 peak':>12s} "
+          f"{'VALU/MFMA':>9s} {'MFMA busy':>9s} {'VALU active':>11s} {'waiting':>8s}")
+    for cls, c in sorted(per.items()):
+        n = len(dur[cls])
+        us = mean(list(dur[cls].values())) / 1e3
+        m, v = mean(c["SQ_INSTS_MFMA"]), mean(c["SQ_INSTS_VALU"])
+        tops = m * 65536.0 / (us * 1e-6) / 1e12            # one v_mfma_i32_32x32x32_i8 = 32*32*32 MACs
+        busy_cu, wave_cyc = mean(c["SQ_BUSY_CU_CYCLES"]), mean(c["SQ_WAVE_CYCLES"])
+        print(f"{cls:24s} {n:8d} {us:7.1f} {m:10.0f} {tops:12.1f} {tops / 5000.0:12.3f} {(v - m) / m:9.1f} "
+              f"{mean(c['SQ_VALU_MFMA_BUSY_CYCLES']) / (4.0 * busy_cu):9.3f} {mean(c['SQ_ACTIVE_INST_VALU']) / wave_cyc:11.3f} "
+              f"{mean(c['SQ_WAIT_INST_ANY']) / wave_cyc:8.3f}")
+    print("\nMFMA inst: v_mfma_i32_32x32x32_i8 issued (all waves); issued TOP/s = MFMA inst * 65536 ops / duration (includes the\n"
+          "rows and columns a tile pads); VALU/MFMA: other vector instructions per MFMA (SQ_INSTS_VALU counts the MFMAs too);\n"
+          "MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / (4 SIMDs * SQ_BUSY_CU_CYCLES); VALU active, waiting = SQ_ACTIVE_INST_VALU, SQ_WAIT_INST_ANY\n"
+          "over SQ_WAVE_CYCLES (share of wave lifetime).")
+    if bench:
+        g = bench.get("gemm_all", {})
+        print(f"\nplain run of bench.py: GEMMs {g.get('TOPs')} TOP/s algorithmic = {g.get('frac_int8_peak')} of the int8 peak, "
+              f"{g.get('step_ms')} ms of a {bench['ms_per_step']} ms step")
+
+
 if __name__ == "__main__":
     if len(sys.argv) >= 3 and sys.argv[1] == "stats":
         stats(*sys.argv[2:4])
+    elif len(sys.argv) >= 3 and sys.argv[1] == "mfma":
+        mfma(*sys.argv[2:4])
     elif len(sys.argv) >= 5 and sys.argv[1] == "traffic":
         traffic(*sys.argv[2:6])
     else:
