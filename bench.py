@@ -66,11 +66,14 @@ def measured_traffic(kernel):
                         source="profiles/hbm_traffic_c3_stack.txt")
 
 
-def serving_shape_kernels(shape, seed, reps=20):
-    """The same kernels at the batched-serving shape (batch 16 x 704 tokens of the 7B model), where a
-    call moves >= 90 MB and the bandwidth kernels are out of the launch-latency regime: each kernel is
-    launched `reps` times back to back between one event pair, and its algorithmic bytes (or ops) per
-    second are set against the HBM (or int8 MFMA) peak.  Supplementary to the headline figure."""
+def bandwidth_kernels(shape, seed, reps=12, with_gemm=False):
+    """The bandwidth-bound kernels of the path at the batched-serving row count (batch 16 x 704 tokens
+    of the 7B model = 11264 rows), where a call moves >= 90 MB: at batch 1 the same kernels move 0.1-10 MB
+    per launch and sit in the launch-latency regime, so their GB/s there says nothing about them.
+    Each kernel is launched `reps` times between one event pair on the launch stream, rotating over
+    several input buffers that together exceed the 256 MB last-level cache, so the reads come from
+    HBM; its algorithmic bytes per second are set against the HBM peak.  Outside the timed region of
+    the headline figure."""
     import torch
     from paper_2604_17320_amd import binding as qb, workloads as wl
     from paper_2604_17320_amd.model import KVCache4, PackedLinear
@@ -79,7 +82,9 @@ def serving_shape_kernels(shape, seed, reps=20):
     g = torch.Generator(device="cuda")
     g.manual_seed(seed + 77)
     rnd = lambda *shp: torch.randn(shp, generator=g, device="cuda", dtype=torch.float32).to(torch.float16)
-    x, qkv, gu = rnd(M, d), rnd(M, 3 * d), rnd(M, 2 * F)
+    xs = [rnd(M, d) for _ in range(4)]                   # 4 x 92 MB
+    qkvs = [rnd(M, 3 * d) for _ in range(2)]             # 2 x 277 MB
+    gus = [rnd(M, 2 * F) for _ in range(2)]              # 2 x 496 MB
     gamma = torch.ones(d, dtype=torch.float32, device="cuda")
     qa = torch.empty((M, max(d, F) // 2), dtype=torch.uint8, device="cuda")
     sa, sq, rq = (torch.empty(M, dtype=torch.float32, device="cuda") for _ in range(3))
@@ -87,39 +92,57 @@ def serving_shape_kernels(shape, seed, reps=20):
     cosT, sinT = torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda()
     pos = torch.arange(N, dtype=torch.int32, device="cuda").repeat(B)
     q_rot, khat, vhat = (torch.empty((M, d), dtype=torch.float16, device="cuda") for _ in range(3))
+    kv_in = [(rnd(M, d), rnd(M, d)) for _ in range(2)]   # 2 x 184 MB
     kc, vc = (torch.empty((M, d // 2), dtype=torch.uint8, device="cuda") for _ in range(2))
     ks, vs = (torch.empty((M, d // 64), dtype=torch.float16, device="cuda") for _ in range(2))
     n_keep = 173 + 128
     keep = torch.arange(n_keep, dtype=torch.int32, device="cuda").mul(2).repeat(B).contiguous()
     cache = KVCache4(B, n_keep + 66, H, dh)
-    w = torch.randn((3 * d, d), generator=g, device="cuda", dtype=torch.float32) * 0.02
-    lin = PackedLinear.from_fp32(w)
-    del w
-    y = torch.empty((M, 3 * d), dtype=torch.float16, device="cuda")
     q1 = rnd(B, d)
     o1 = torch.empty((B, d), dtype=torch.float16, device="cuda")
 
-    def append():
+    def append(i):
         cache.reset()
-        qb.quota_kv_quant_append(khat, vhat, B, N, H, dh, keep, n_keep, cache.desc)
+        k_, v_ = kv_in[i % 2]
+        qb.quota_kv_quant_append(k_, v_, B, N, H, dh, keep, n_keep, cache.desc)
 
-    def decode_attn():
+    def decode_attn(i):
         cache.desc.len = n_keep + 65           # pruned prefix + 65 decoded tokens
         qb.quota_attention_decode(q1, cache.desc, o1)
 
     Md = float(M) * d
     cases = [
-        ("quantize_act", lambda: qb.quota_quantize_act(x, M, d, d, qa, sa, sq, rq), 2.5 * Md, 0),
-        ("rmsnorm_quantize_act", lambda: qb.quota_rmsnorm_quantize_act(x, M, d, d, gamma, 1e-5, qa, sa, sq, rq), 2.5 * Md, 0),
-        ("silu_mul_quantize_act", lambda: qb.quota_silu_mul_quantize_act(gu, M, F, qa, sa), 4.5 * M * F, 0),
-        ("rope_kv_quant", lambda: qb.quota_rope_kv_quant(qkv, M, H, dh, pos, cosT, sinT, N, q_rot, khat, vhat, kc, ks, vc, vs),
-         Md * (6 + 6 + 1 + 1.0 / 16), 0),
-        ("kv_quant_append", append, B * n_keep * d * (4 + 1 + 1.0 / 16), 0),
-        ("attention_decode", decode_attn, B * (n_keep + 65) * (d + d / 16.0), 0),
-        ("w4a4_gemm qkv", lambda: qb.quota_w4a4_gemm(qa, sa, M, lin.desc, y, 3 * d), 0, 2.0 * M * 3 * d * d),
+        ("quantize_act", lambda i: qb.quota_quantize_act(xs[i % 4], M, d, d, qa, sa), 2.5 * Md),
+        ("quantize_act (+ m_mag, m_res)", lambda i: qb.quota_quantize_act(xs[i % 4], M, d, d, qa, sa, sq, rq), 2.5 * Md),
+        ("rmsnorm_quantize_act", lambda i: qb.quota_rmsnorm_quantize_act(xs[i % 4], M, d, d, gamma, 1e-5, qa, sa), 2.5 * Md),
+        ("rmsnorm_quantize_act (+ m_mag, m_res)",
+         lambda i: qb.quota_rmsnorm_quantize_act(xs[i % 4], M, d, d, gamma, 1e-5, qa, sa, sq, rq), 2.5 * Md),
+        ("silu_mul_quantize_act", lambda i: qb.quota_silu_mul_quantize_act(gus[i % 2], M, F, qa, sa), 4.5 * M * F),
+        ("rope_kv_quant", lambda i: qb.quota_rope_kv_quant(qkvs[i % 2], M, H, dh, pos, cosT, sinT, N, q_rot, khat, vhat, kc, ks, vc, vs),
+         Md * (6 + 6 + 1 + 1.0 / 16)),
+        ("kv_quant_append", append, B * n_keep * d * (4 + 1 + 1.0 / 16)),
+        ("attention_decode", decode_attn, B * (n_keep + 65) * (d + d / 16.0)),
     ]
     out = {}
-    for name, fn, nbytes, ops in cases:
+    for name, fn, nbytes in cases:
+        fn(0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        out[name] = dict(avg_us=round(us, 2), MB=round(nbytes / 1e6, 1), GBps=round(nbytes / us / 1e3, 1),
+                         frac_hbm_peak=round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4))
+    if with_gemm:
+        w = torch.randn((3 * d, d), generator=g, device="cuda", dtype=torch.float32) * 0.02
+        lin = PackedLinear.from_fp32(w)
+        del w
+        y = torch.empty((M, 3 * d), dtype=torch.float16, device="cuda")
+        qb.quota_quantize_act(xs[0], M, d, d, qa, sa)
+        fn = lambda: qb.quota_w4a4_gemm(qa, sa, M, lin.desc, y, 3 * d)
         fn()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -128,26 +151,25 @@ def serving_shape_kernels(shape, seed, reps=20):
             fn()
         e1.record()
         torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / reps
-        rec = dict(avg_us=round(us, 2))
-        if nbytes:
-            rec.update(GBps=round(nbytes / us / 1e3, 1), frac_hbm_peak=round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4))
-        if ops:
-            rec.update(TOPs=round(ops / us / 1e6, 1), frac_int8_peak=round(ops / us / 1e6 / PEAK_INT8_TOPS, 4))
-        out[name] = rec
-    return dict(shape=f"batch {B} x {N} tokens, d={d}, F={F} ({M} rows)", reps=reps, kernels=out)
+        us, ops = e0.elapsed_time(e1) * 1e3 / reps, 2.0 * M * 3 * d * d
+        out["w4a4_gemm qkv"] = dict(avg_us=round(us, 2), TOPs=round(ops / us / 1e6, 1),
+                                    frac_int8_peak=round(ops / us / 1e6 / PEAK_INT8_TOPS, 4))
+    return dict(shape=f"batch {B} x {N} tokens, d={d}, F={F} ({M} rows)", reps=reps,
+                note="algorithmic bytes (inputs once + outputs once, int4 as half bytes) / event time; inputs rotate over "
+                     "buffers larger than the last-level cache", kernels=out)
 
 
-def serving_decode(shape, stack, budgets, seed, steps=16):
+def serving_decode(shape, stack, budgets, seed, steps=32):
     """Batched-serving shape end to end on the same weights: batch 16 x (576 + 128) tokens pruned
-    prefill, then `steps` decode steps (random next-token embeddings) over the pruned 4-bit caches.
-    Supplementary: decode tokens/s and the weight-streaming bound of a step."""
+    prefill, then `steps` decode steps (random next-token embeddings) over the pruned 4-bit caches,
+    once as eager launches and once as replays of ONE captured step (the cache length then lives
+    on the device).  Supplementary: decode tokens/s and the weight-streaming bound of a step."""
     import torch
-    from paper_2604_17320_amd import workloads as wl
+    from paper_2604_17320_amd import binding as qb
     from paper_2604_17320_amd.model import PrefillStack
     B, Nv, Nt = 16, shape.Nv, 128
     N = Nv + Nt
-    big = PrefillStack(stack.layers, B, N, 0, Nv, budgets, decode_capacity=steps + 3)
+    big = PrefillStack(stack.layers, B, N, 0, Nv, budgets, decode_capacity=2 * steps + 8)
     g = torch.Generator(device="cuda")
     g.manual_seed(seed + 99)
     x0 = torch.randn((B * N, shape.d), generator=g, device="cuda", dtype=torch.float32).to(torch.float16)
@@ -167,19 +189,40 @@ def serving_decode(shape, stack, budgets, seed, steps=16):
         pn = torch.full((B,), N + 1 + i, dtype=torch.int32, device="cuda")
         big.decode(xs[1 + i], pn)
     torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / steps
-    from paper_2604_17320_amd import binding as qb
+    eager_ms = (time.perf_counter() - t0) * 1e3 / steps
     qb.quota_profile_begin(20 * len(stack.layers) + 16)
     big.decode(xs[0], torch.full((B,), N + 1 + steps, dtype=torch.int32, device="cuda"))
     kstats = qb.quota_profile_collect()
-    gpu_ms = sum(v["total_ms"] for v in kstats.values())
     per_kernel = {k: round(v["total_ms"] * 1e3 / v["launches"], 2) for k, v in kstats.items()}
+    # the same loop as replays of one captured step
+    step_dev = big.begin_stepped_decode(steps + 2)
+    x_in = xs[0].clone()
+    pn = torch.full((B,), N + 2 + steps, dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        big.decode(x_in, pn)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        big.decode(x_in, pn)
+        qb.quota_advance_step(step_dev)
+        pn.add_(1)
+    step_dev.zero_()
+    graph.replay()                              # warm-up replay
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
     wbytes = sum(l.weight_bytes() for l in stack.layers)
-    kv_bytes = sum(B * c.len * (shape.d + shape.d // 16) for c in big.caches)
+    kv_bytes = sum(B * (c.len + steps // 2) * (shape.d + shape.d // 16) for c in big.caches)
+    big.end_stepped_decode(steps + 1)
     return dict(shape=f"batch {B} x ({Nv} + {Nt}) tokens, {len(stack.layers)} layers", prefill_ms=round(prefill_ms, 2),
                 prefill_tokens_per_s=round(B * N / prefill_ms * 1e3, 1), decode_steps=steps,
                 decode_ms_per_step=round(ms, 3), decode_tokens_per_s=round(B / ms * 1e3, 1),
-                decode_kernel_ms_per_step=round(gpu_ms, 3), decode_avg_us_per_kernel=per_kernel,
+                decode_eager_ms_per_step=round(eager_ms, 3), hip_graph=True,
+                decode_avg_us_per_kernel=per_kernel,
                 weight_bytes_per_step=wbytes, kv_bytes_per_step=kv_bytes,
                 hbm_bound_ms=round((wbytes + kv_bytes) / (PEAK_HBM_GBS * 1e9) * 1e3, 3),
                 frac_hbm_peak=round((wbytes + kv_bytes) / (ms * 1e-3) / (PEAK_HBM_GBS * 1e9), 4))
@@ -417,8 +460,8 @@ def main():
                              frac_int8_peak=round(gemm_ops / (gemm_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 4)
                              if gemm_ms else None, step_ms=round(gemm_ms / args.profile_steps, 4)),
                kernels=kern)
+    out["bandwidth_kernels"] = bandwidth_kernels(shape, args.seed, with_gemm=args.serving_shape)
     if args.serving_shape:
-        out["serving_shape_kernels"] = serving_shape_kernels(shape, args.seed)
         if args.config == "c3":
             out["serving_decode"] = serving_decode(shape, stack, budgets, args.seed)
     if not args.no_cpu:

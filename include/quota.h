@@ -143,6 +143,17 @@ typedef struct quota_kv_cache {
     void *k_scales;
     uint8_t *v_codes;
     void *v_scales;
+    /* Decode loops captured in a HIP graph cannot read a host field that
+     * changes from step to step.  When step_dev (device int32, one value) is
+     * not null, the decode calls take the cache length as len + *step_dev,
+     * read by the kernels: quota_decode_layer appends at that row and does NOT
+     * advance len, quota_attention_decode(_gqa) attends over len + *step_dev
+     * + 1 rows.  The host checks len + max_steps <= capacity when the call is
+     * made and the kernels clamp *step_dev to [0, max_steps - 1].  The caller
+     * advances *step_dev between steps (quota_advance_step, capturable) and
+     * folds the steps into len when the loop ends.  Null: len alone counts. */
+    const int32_t *step_dev;
+    int max_steps;
 } quota_kv_cache;
 
 /* Rotates q and k (rotate-half pairing (i, i+dh/2)) by the angle tables
@@ -390,6 +401,10 @@ int quota_attention_decode(const void *q_f16, const quota_kv_cache *cache,
  * Requires Hq % cache->H == 0. */
 int quota_attention_decode_gqa(const void *q_f16, int Hq, const quota_kv_cache *cache,
                                void *o_f16, void *stream);
+
+/* *step_dev += 1 on the stream (a one-thread kernel, so it can be captured in
+ * the same HIP graph as the decode step that reads it). */
+int quota_advance_step(int32_t *step_dev, void *stream);
 
 size_t quota_decode_workspace_bytes(const quota_layer *L, int B);
 

@@ -33,7 +33,7 @@ class Weights(C.Structure):
 class KVCache(C.Structure):
     _fields_ = [("B", C.c_int), ("capacity", C.c_int), ("H", C.c_int), ("dh", C.c_int),
                 ("len", C.c_int), ("k_codes", C.c_void_p), ("k_scales", C.c_void_p),
-                ("v_codes", C.c_void_p), ("v_scales", C.c_void_p)]
+                ("v_codes", C.c_void_p), ("v_scales", C.c_void_p), ("step_dev", C.c_void_p), ("max_steps", C.c_int)]
 
 
 class ScoreParams(C.Structure):
@@ -272,6 +272,10 @@ def quota_attention_decode(q, cache: KVCache, o):
 def quota_attention_decode_gqa(q, Hq, cache: KVCache, o):
     _check(lib().quota_attention_decode_gqa(_ptr(q, torch.float16), int(Hq), C.byref(cache),
                                             _ptr(o, torch.float16), _stream()), "quota_attention_decode_gqa")
+
+
+def quota_advance_step(step_dev):
+    _check(lib().quota_advance_step(_ptr(step_dev, torch.int32), _stream()), "quota_advance_step")
 
 
 def quota_decode_workspace_bytes(L: Layer, B):

@@ -101,3 +101,17 @@ __device__ __forceinline__ int code_from(float r)
     r = fminf(fmaxf(r, -8.0f), 7.0f);
     return (int)r;
 }
+
+// The int4 code of a scaled value t = x * (7 / absmax), without a round / convert / mask chain:
+// clamp to [-8, 7] first (the bounds are integers, so clamping commutes with rounding to integer),
+// then add 1.5 * 2^23 -- in that binade one unit in the last place is 1, so the fp32 add itself
+// rounds to the nearest integer, ties to even, and the low mantissa bits of the sum hold the code in
+// two's complement.  code_bits(t) & 0xF is the packed nibble; code_float(bits) the code as a float.
+#define ROW_MAGIC 12582912.0f
+__device__ __forceinline__ uint32_t code_bits(float t)
+{
+    t = fminf(fmaxf(t, -8.0f), 7.0f);          // NaN -> -8, as in code_from
+    return __float_as_uint(t + ROW_MAGIC);
+}
+__device__ __forceinline__ float code_float(uint32_t bits) { return __uint_as_float(bits) - ROW_MAGIC; }
+

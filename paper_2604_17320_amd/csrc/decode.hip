@@ -8,7 +8,7 @@
 
 namespace {
 
-constexpr int DEC_LMAX = QUOTA_MAX_DECODE_ROWS;      // cached rows one workgroup can softmax over (scores live in LDS)
+constexpr int DEC_LMAX = QUOTA_MAX_DECODE_ROWS;      // cached rows per sequence the decode calls accept
 
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 
@@ -43,116 +43,190 @@ __global__ __launch_bounds__(256) void kv_append_rows_kernel(
     }
 }
 
-// One workgroup per (head, sequence).  Pass 1: a thread per cached token computes
-// q . k_hat (k_hat = fp16(code * scale), the value the quantizer defines) and the scores
-// go to LDS; block max / sum; pass 2: DH/8 threads per token each own 8 channels of V and
-// accumulate p_t * v_hat_t over their share of the tokens; the token lanes are then summed
-// through LDS in a fixed order.
+// One workgroup per (K/V head, sequence); it serves the `rep` query heads that share the K/V head,
+// RC at a time, so a K/V row is fetched from HBM once per group of query heads.  The cached rows
+// are walked in tiles of DEC_TILE tokens with a running softmax (maximum, sum, rescaled output), so
+// the scores of one tile are all the LDS the kernel needs, whatever the cache length.
+//   scores:  DH/32 lanes per token, each loads 16 contiguous bytes of the token's K codes (32
+//            channels) -- a wave reads whole 64- or 32-byte row segments -- dequantizes them as
+//            packed fp16 pairs and dots them with the query; the lanes of a token add up by shuffles;
+//   output:  the same lanes own 32 channels of V each and accumulate p * v_hat over their share of
+//            the tokens; the token lanes are summed through LDS in a fixed order at the end.
+// step_dev (optional): the cache length is len + *step_dev (a HIP-graph-captured decode loop keeps
+// its step count on the device).
+constexpr int DEC_TILE = 1024;
+constexpr int DEC_RC = 2;           // query heads served per pass over the K/V rows
+
 template <int DH>
 __global__ __launch_bounds__(256) void decode_attention_kernel(
     const f16 *__restrict__ q, int d, int dkv, int rep, const uint32_t *__restrict__ kc,
     const f16 *__restrict__ ks, const uint32_t *__restrict__ vc, const f16 *__restrict__ vs, int capacity,
-    int L, f16 *__restrict__ o)
+    int len, const int32_t *__restrict__ step_dev, int max_steps, f16 *__restrict__ o)
 {
+    constexpr int PPT = DH / 32;            // 16-byte pieces (lanes) per token and head
+    constexpr int TP = 256 / PPT;           // tokens per pass of the workgroup
     constexpr int WPT = DH / 8;             // packed dwords per token and head
     constexpr int GPT = DH / 64;            // scale groups per token and head
-    constexpr int TL = 256 / WPT;           // token lanes of pass 2
-    __shared__ h2 qp[DH / 2];               // q as pairs: qp[4 i + e] = (q[8 i + e], q[8 i + e + 4])
-    __shared__ float sc[DEC_LMAX];
-    __shared__ float red[TL * DH];
-    __shared__ float wred[8];
-    const int hq = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-    const int h = hq / rep;                 // K/V head read by query head hq (rep query heads per K/V head)
+    __shared__ h2 qp[DEC_RC][DH / 2];       // q as pairs: qp[r][4 i + e] = (q[8 i + e], q[8 i + e + 4])
+    __shared__ float sc[DEC_RC][DEC_TILE];
+    __shared__ float red[TP * 32 * PPT / 2];          // one half of the token lanes at a time
+    __shared__ float wred[2][DEC_RC][4];
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, wave = tid >> 6;
+    const int piece = tid % PPT, tl = tid / PPT;
     const int n32 = dkv >> 3, ng = dkv >> 6;
-    if (tid < DH / 2) {
-        const f16 *qh = q + (size_t)b * d + hq * DH + 8 * (tid >> 2) + (tid & 3);
-        qp[tid] = h2{qh[0], qh[4]};
-    }
-    __syncthreads();
+    int L = len;
+    if (step_dev) L += min(max(*step_dev, 0), max_steps - 1) + 1;      // the row this step appended included
     const float scale = 1.0f / sqrtf((float)DH);
+    const size_t row0 = (size_t)b * capacity;
 
-    float mx = -INFINITY;
-    for (int t = tid; t < L; t += 256) {
-        const size_t row = (size_t)b * capacity + t;
-        const uint32_t *kw = kc + row * n32 + h * WPT;
-        const f16 *sp = ks + row * ng + h * GPT;
-        float dot = 0.0f;
+    for (int r0 = 0; r0 < rep; r0 += DEC_RC) {
+        const int nr = min(DEC_RC, rep - r0);
+        __syncthreads();                    // qp, sc, red of the previous pass are done with
+        if (tid < DEC_RC * (DH / 2)) {
+            const int r = tid / (DH / 2), i = tid % (DH / 2);
+            const int hq = min(h * rep + r0 + r, h * rep + rep - 1);
+            const f16 *qh = q + (size_t)b * d + hq * DH + 8 * (i >> 2) + (i & 3);
+            qp[r][i] = h2{qh[0], qh[4]};
+        }
+        __syncthreads();
+        float m_run[DEC_RC], l_run[DEC_RC], acc[DEC_RC][32];
 #pragma unroll
-        for (int g = 0; g < GPT; ++g) {
-            const _Float16 sh = sp[g];
-            const h2 s2 = h2{sh, sh};
+        for (int r = 0; r < DEC_RC; ++r) {
+            m_run[r] = -INFINITY;
+            l_run[r] = 0.0f;
 #pragma unroll
-            for (int w4 = 0; w4 < 2; ++w4) {
-                const uint4 pk = *reinterpret_cast<const uint4 *>(kw + 8 * g + 4 * w4);
+            for (int e = 0; e < 32; ++e) acc[r][e] = 0.0f;
+        }
+        for (int t0 = 0; t0 < L; t0 += DEC_TILE) {
+            const int tn = min(DEC_TILE, L - t0);
+            // ---- scores of the tile
+            float mx[DEC_RC];
+#pragma unroll
+            for (int r = 0; r < DEC_RC; ++r) mx[r] = -INFINITY;
+            for (int tb = 0; tb < tn; tb += TP) {
+                const int t = tb + tl;
+                const bool ok = t < tn;
+                const size_t row = row0 + t0 + (ok ? t : 0);
+                const uint4 pk = *reinterpret_cast<const uint4 *>(kc + row * n32 + h * WPT + 4 * piece);
+                const _Float16 sh = ks[row * ng + h * GPT + (piece >> 1)];
+                const h2 s2 = h2{sh, sh};
                 const uint32_t ww[4] = {pk.x ^ 0x88888888u, pk.y ^ 0x88888888u, pk.z ^ 0x88888888u,
                                         pk.w ^ 0x88888888u};
+                float dot[DEC_RC];
+#pragma unroll
+                for (int r = 0; r < DEC_RC; ++r) dot[r] = 0.0f;
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)     // channels (8i + e, 8i + e + 4) of this 32-channel piece
-                        dot = __builtin_amdgcn_fdot2(qp[(64 * g + 32 * w4 + 8 * i) / 2 + e],
-                                                     dequant_pair(ww[i], e, s2), dot, false);
+                    for (int e = 0; e < 4; ++e) {       // channels (8 id + e, 8 id + e + 4), id = 4 piece + i
+                        const h2 kh = dequant_pair(ww[i], e, s2);
+#pragma unroll
+                        for (int r = 0; r < DEC_RC; ++r)
+                            dot[r] = __builtin_amdgcn_fdot2(qp[r][4 * (4 * piece + i) + e], kh, dot[r], false);
+                    }
+#pragma unroll
+                for (int r = 0; r < DEC_RC; ++r) {
+                    float v = dot[r];
+                    v += __shfl_xor(v, 1, 64);
+                    if (PPT == 4) v += __shfl_xor(v, 2, 64);
+                    v *= scale;
+                    if (ok && piece == 0) sc[r][t] = v;
+                    if (ok) mx[r] = fmaxf(mx[r], v);
+                }
             }
-        }
-        dot *= scale;
-        sc[t] = dot;
-        mx = fmaxf(mx, dot);
-    }
-    mx = wave_max(mx);
-    if ((tid & 63) == 0) wred[tid >> 6] = mx;
-    __syncthreads();
-    mx = fmaxf(fmaxf(wred[0], wred[1]), fmaxf(wred[2], wred[3]));
-    float sum = 0.0f;
-    for (int t = tid; t < L; t += 256) {
-        const float p = __expf(sc[t] - mx);
-        sc[t] = p;
-        sum += p;
-    }
-    sum = wave_sum(sum);
-    if ((tid & 63) == 0) wred[4 + (tid >> 6)] = sum;
-    __syncthreads();                        // also publishes every sc[t]
-    const float inv = 1.0f / (((wred[4] + wred[5]) + wred[6]) + wred[7]);
-
-    const int cl = tid % WPT, tl = tid / WPT;
-    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    constexpr int UN = 8;                   // tokens in flight per thread: loads first, then the math
-    for (int t0 = tl; t0 < L; t0 += TL * UN) {
-        uint32_t w[UN];
-        f16 sv[UN];
-        float pv[UN];
 #pragma unroll
-        for (int i = 0; i < UN; ++i) {
-            const int t = t0 + TL * i;
-            const bool ok = t < L;
-            const size_t row = (size_t)b * capacity + (ok ? t : 0);
-            w[i] = vc[row * n32 + h * WPT + cl];
-            sv[i] = vs[row * ng + h * GPT + (cl >> 3)];
-            pv[i] = ok ? sc[t] : 0.0f;
-        }
-#pragma unroll
-        for (int i = 0; i < UN; ++i) {
-            const uint32_t wx = w[i] ^ 0x88888888u;
-            const h2 s2 = h2{sv[i], sv[i]};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const h2 vh = dequant_pair(wx, e, s2);
-                acc[e] = fmaf(pv[i], (float)vh[0], acc[e]);
-                acc[e + 4] = fmaf(pv[i], (float)vh[1], acc[e + 4]);
+            for (int r = 0; r < DEC_RC; ++r) {
+                mx[r] = wave_max(mx[r]);
+                if ((tid & 63) == 0) wred[0][r][wave] = mx[r];
             }
-        }
-    }
+            __syncthreads();                // scores and wave maxima visible
+            float alpha[DEC_RC], m_new[DEC_RC], sum[DEC_RC];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) red[tl * DH + 8 * cl + e] = acc[e];
-    __syncthreads();
-    if (tid < DH) {
-        float v = 0.0f;
+            for (int r = 0; r < DEC_RC; ++r) {
+                const float tm = fmaxf(fmaxf(wred[0][r][0], wred[0][r][1]), fmaxf(wred[0][r][2], wred[0][r][3]));
+                m_new[r] = fmaxf(m_run[r], tm);
+                alpha[r] = __expf(m_run[r] - m_new[r]);      // 0 on the first tile
+                m_run[r] = m_new[r];
+                sum[r] = 0.0f;
+                for (int t = tid; t < tn; t += 256) {
+                    const float p = __expf(sc[r][t] - m_new[r]);
+                    sc[r][t] = p;
+                    sum[r] += p;
+                }
+                sum[r] = wave_sum(sum[r]);
+                if ((tid & 63) == 0) wred[1][r][wave] = sum[r];
+            }
+            __syncthreads();                // probabilities and wave sums visible
+#pragma unroll
+            for (int r = 0; r < DEC_RC; ++r) {
+                l_run[r] = l_run[r] * alpha[r] + (((wred[1][r][0] + wred[1][r][1]) + wred[1][r][2]) + wred[1][r][3]);
+#pragma unroll
+                for (int e = 0; e < 32; ++e) acc[r][e] *= alpha[r];
+            }
+            // ---- p * v_hat of the tile
+            for (int tb = 0; tb < tn; tb += TP) {
+                const int t = tb + tl;
+                const bool ok = t < tn;
+                const size_t row = row0 + t0 + (ok ? t : 0);
+                const uint4 pk = *reinterpret_cast<const uint4 *>(vc + row * n32 + h * WPT + 4 * piece);
+                const _Float16 sh = vs[row * ng + h * GPT + (piece >> 1)];
+                const h2 s2 = h2{sh, sh};
+                const uint32_t ww[4] = {pk.x ^ 0x88888888u, pk.y ^ 0x88888888u, pk.z ^ 0x88888888u,
+                                        pk.w ^ 0x88888888u};
+                float pv[DEC_RC];
+#pragma unroll
+                for (int r = 0; r < DEC_RC; ++r) pv[r] = ok ? sc[r][t] : 0.0f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const h2 vh = dequant_pair(ww[i], e, s2);
+#pragma unroll
+                        for (int r = 0; r < DEC_RC; ++r) {
+                            acc[r][8 * i + e] = fmaf(pv[r], (float)vh[0], acc[r][8 * i + e]);
+                            acc[r][8 * i + e + 4] = fmaf(pv[r], (float)vh[1], acc[r][8 * i + e + 4]);
+                        }
+                    }
+            }
+            __syncthreads();                // the tile's scores have been consumed
+        }
+        // ---- the token lanes meet in LDS, half of them at a time, summed in lane order
+        for (int r = 0; r < nr; ++r) {
+            float out = 0.0f;
+            for (int half = 0; half < 2; ++half) {
+                __syncthreads();
+                if (tl / (TP / 2) == half) {
+#pragma unroll
+                    for (int e = 0; e < 32; ++e) red[((tl % (TP / 2)) * PPT + piece) * 32 + e] = acc[r][e];
+                }
+                __syncthreads();
+                if (tid < DH) {
+                    const int pc = tid >> 5, e = tid & 31;
 #pragma unroll 4
-        for (int i = 0; i < TL; ++i) v += red[i * DH + tid];
-        o[(size_t)b * d + hq * DH + tid] = (f16)(v * inv);
+                    for (int i = 0; i < TP / 2; ++i) out += red[(i * PPT + pc) * 32 + e];
+                }
+            }
+            if (tid < DH) o[(size_t)b * d + (h * rep + r0 + r) * DH + tid] = (f16)(out / l_run[r]);
+        }
     }
 }
 
+__global__ void advance_step_kernel(int32_t *step) { *step += 1; }
+
 }  // namespace
+
+int quota_internal_advance_step(int32_t *step_dev, hipStream_t st)
+{
+    advance_step_kernel<<<1, 1, 0, st>>>(step_dev);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    return QUOTA_OK;
+}
+
+extern "C" int quota_advance_step(int32_t *step_dev, void *stream)
+{
+    if (!step_dev) return QUOTA_ERR_NULL;
+    return quota_internal_advance_step(step_dev, (hipStream_t)stream);
+}
 
 int quota_internal_kv_append_rows(int d, const uint8_t *skc, const void *sks, const uint8_t *svc,
                                   const void *svs, quota_kv_cache *c, hipStream_t st)
@@ -173,25 +247,24 @@ extern "C" int quota_attention_decode_gqa(const void *q_f16, int Hq, const quota
     if (!q_f16 || !cache || !o_f16 || !cache->k_codes || !cache->k_scales || !cache->v_codes ||
         !cache->v_scales)
         return QUOTA_ERR_NULL;
-    if (cache->B <= 0 || cache->H <= 0 || Hq <= 0 || cache->len <= 0 || cache->len > cache->capacity)
+    const bool stepped = cache->step_dev != nullptr;     // length = len + *step_dev + 1 (read on the device)
+    if (cache->B <= 0 || cache->H <= 0 || Hq <= 0 || cache->len > cache->capacity ||
+        (stepped ? cache->len < 0 || cache->max_steps <= 0 || cache->len + cache->max_steps > cache->capacity
+                 : cache->len <= 0))
         return QUOTA_ERR_INVALID_ARG;
-    if ((cache->dh != 64 && cache->dh != 128) || cache->len > DEC_LMAX || Hq % cache->H != 0)
+    const int longest = stepped ? cache->len + cache->max_steps : cache->len;
+    if ((cache->dh != 64 && cache->dh != 128) || longest > DEC_LMAX || Hq % cache->H != 0)
         return QUOTA_ERR_SHAPE;
     const int d = Hq * cache->dh, dkv = cache->H * cache->dh, rep = Hq / cache->H;
     hipStream_t st = (hipStream_t)stream;
-    const double rows = (double)cache->B * cache->len;
+    const double rows = (double)cache->B * longest;
     ProfScope prof(QUOTA_K_ATTENTION_DECODE, 4.0 * rows * d, rows * (dkv + dkv / 16.0) + 4.0 * cache->B * d, st);
-    dim3 grid(Hq, cache->B), block(256);
-    if (cache->dh == 128)
-        decode_attention_kernel<128><<<grid, block, 0, st>>>(
-            (const f16 *)q_f16, d, dkv, rep, (const uint32_t *)cache->k_codes, (const f16 *)cache->k_scales,
-            (const uint32_t *)cache->v_codes, (const f16 *)cache->v_scales, cache->capacity,
-            cache->len, (f16 *)o_f16);
-    else
-        decode_attention_kernel<64><<<grid, block, 0, st>>>(
-            (const f16 *)q_f16, d, dkv, rep, (const uint32_t *)cache->k_codes, (const f16 *)cache->k_scales,
-            (const uint32_t *)cache->v_codes, (const f16 *)cache->v_scales, cache->capacity,
-            cache->len, (f16 *)o_f16);
+    dim3 grid(cache->H, cache->B), block(256);
+    auto kernel = cache->dh == 128 ? decode_attention_kernel<128> : decode_attention_kernel<64>;
+    kernel<<<grid, block, 0, st>>>(
+        (const f16 *)q_f16, d, dkv, rep, (const uint32_t *)cache->k_codes, (const f16 *)cache->k_scales,
+        (const uint32_t *)cache->v_codes, (const f16 *)cache->v_scales, cache->capacity, cache->len,
+        cache->step_dev, cache->max_steps, (f16 *)o_f16);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
 }

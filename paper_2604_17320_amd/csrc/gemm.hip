@@ -294,6 +294,7 @@ __global__ __launch_bounds__(256, WPE) void w4a4_gemm_kernel(
         const int region = n0 < d ? 0 : (n0 < d + dkv ? 1 : 2);          // tile-uniform
         const int c0 = n0 - (region == 0 ? 0 : (region == 1 ? d : d + dkv));
         const int CPH = qe.dh >> 3, HALF = CPH >> 1, cpr = dkv >> 3, gpr = dkv >> 6;
+        const int row_step = qe.row_step ? min(max(*qe.row_step, 0), qe.max_steps - 1) : 0;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             if (i) __syncthreads();                   // the previous row block has been read
@@ -346,7 +347,7 @@ __global__ __launch_bounds__(256, WPE) void w4a4_gemm_kernel(
                         uint32_t *codes = region == 1 ? qe.k_codes : qe.v_codes;
                         f16 *scales = region == 1 ? qe.k_scales : qe.v_scales;
                         *reinterpret_cast<uint4 *>(xh + (size_t)m * dkv + col) = hat.u;
-                        const size_t orow = (size_t)m * qe.code_row_stride + qe.code_row_offset;
+                        const size_t orow = (size_t)m * qe.code_row_stride + qe.code_row_offset + row_step;
                         codes[orow * cpr + (col >> 3)] = word;
                         if ((c & 7) == 0) scales[orow * gpr + (col >> 6)] = sc;
                     }
@@ -392,20 +393,22 @@ __global__ __launch_bounds__(256, WPE) void w4a4_gemm_kernel(
 
 // ---- at most 16 rows (the decode step): weight streaming -------------------------------
 // With M <= 16 the GEMM has too few outputs to fill the chip with one accumulation chain per
-// wave, and the fp32 chain over groups cannot be split.  The exact int32 group sums can: the 8
-// waves of a workgroup take every 8th group each (all their loads in flight together), park
-// their 16 x 16 int32 results in LDS, and one thread per output then runs the fp32 chain over
-// those 8 groups in ascending order.  Operands need no LDS: for v_mfma_i32_16x16x64_i8 a lane
-// owns (row or column l % 16, 16 k-slots l / 16), so lane l loads the 16 packed bytes (32
-// codes) number l / 16 of its row's group for A and of its column's group for B, and the
-// even / odd nibble vectors feed two MFMAs.  NB = 16-column blocks per workgroup.
-template <int NB>
+// wave, and the fp32 chain over groups cannot be split.  The exact int32 group sums can: in a round
+// the 8 waves of a workgroup take U groups each (group r0 + 8 u + w for wave w: all their loads in
+// flight together, U * 8 groups = 2 KB of weights per column block and round), park their 16 x 16
+// int32 results in LDS, and one thread per output then runs the fp32 chain over those 8 U groups in
+// ascending order.  Operands need no LDS: for v_mfma_i32_16x16x64_i8 a lane owns (row or column
+// l % 16, 16 k-slots l / 16), so lane l loads the 16 packed bytes (32 codes) number l / 16 of its
+// row's group for A and of its column's group for B, and the even / odd nibble vectors feed two
+// MFMAs.  NB = 16-column blocks per workgroup.
+template <int NB, int U>
 __global__ __launch_bounds__(512) void w4a4_gemv16_kernel(
     const uint8_t *__restrict__ qa, const float *__restrict__ sa, int M, int K, int G,
     const uint4 *__restrict__ wp, const f16 *__restrict__ sw, int N, f16 *__restrict__ y, int ldy,
     const f16 *__restrict__ res, int ldr)
 {
-    __shared__ int accs[8][NB][4][64];
+    constexpr int R = 8 * U;                    // groups per round
+    __shared__ int accs[R][NB][4][64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, c = lane & 15, q = lane >> 4;
     const int n0 = blockIdx.x * 16 * NB, Kb = K >> 1;
     const uint8_t *arow = qa + (size_t)min(c, M - 1) * Kb;
@@ -416,43 +419,53 @@ __global__ __launch_bounds__(512) void w4a4_gemv16_kernel(
     const int om = 4 * (ol >> 4) + oreg, on = n0 + 16 * oj + (ol & 15);
     float y32 = 0.0f;
 
-    uint4 ra, rb[NB];
-    f16 rs[8];
+    uint4 ra[U], rb[U][NB];
+    f16 rs[R];
     auto fetch = [&](int r0) {
-        const int g = min(r0 + wave, G - 1);
-        ra = *reinterpret_cast<const uint4 *>(arow + min(g * 64 + q * 16, Kb - 16));
 #pragma unroll
-        for (int j = 0; j < NB; ++j) rb[j] = wp[((size_t)g * N + n0 + 16 * j + c) * 4 + q];
+        for (int u = 0; u < U; ++u) {
+            const int g = min(r0 + 8 * u + wave, G - 1);
+            ra[u] = *reinterpret_cast<const uint4 *>(arow + min(g * 64 + q * 16, Kb - 16));
+#pragma unroll
+            for (int j = 0; j < NB; ++j) rb[u][j] = wp[((size_t)g * N + n0 + 16 * j + c) * 4 + q];
+        }
         if (owner) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) rs[i] = sw[(size_t)min(r0 + i, G - 1) * N + on];
+            for (int i = 0; i < R; ++i) rs[i] = sw[(size_t)min(r0 + i, G - 1) * N + on];
         }
     };
     fetch(0);
-    for (int r0 = 0; r0 < G; r0 += 8) {
-        uint4 alo, ahi;
-        unpack16(ra, alo, ahi);
-        i32x4 acc[NB];
+    for (int r0 = 0; r0 < G; r0 += R) {
+        i32x4 acc[U][NB];
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            uint4 blo, bhi;
-            unpack16(rb[j], blo, bhi);
-            acc[j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(as_i32x4(alo), as_i32x4(blo), i32x4{0, 0, 0, 0}, 0, 0, 0);
-            acc[j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(as_i32x4(ahi), as_i32x4(bhi), acc[j], 0, 0, 0);
+        for (int u = 0; u < U; ++u) {
+            uint4 alo, ahi;
+            unpack16(ra[u], alo, ahi);
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                uint4 blo, bhi;
+                unpack16(rb[u][j], blo, bhi);
+                acc[u][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(as_i32x4(alo), as_i32x4(blo), i32x4{0, 0, 0, 0}, 0, 0, 0);
+                acc[u][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(as_i32x4(ahi), as_i32x4(bhi), acc[u][j], 0, 0, 0);
+            }
         }
-        float sc[8];
+        float sc[R];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) sc[i] = r0 + i < G ? (float)rs[i] : 0.0f;
-        const bool live = r0 + wave < G;
-        if (r0 + 8 < G) fetch(r0 + 8);              // next round's loads fly during the exchange
+        for (int i = 0; i < R; ++i) sc[i] = r0 + i < G ? (float)rs[i] : 0.0f;
+        bool live[U];
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
+        for (int u = 0; u < U; ++u) live[u] = r0 + 8 * u + wave < G;
+        if (r0 + R < G) fetch(r0 + R);              // next round's loads fly during the exchange
 #pragma unroll
-            for (int i = 0; i < 4; ++i) accs[wave][j][i][lane] = live ? acc[j][i] : 0;
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) accs[8 * u + wave][j][i][lane] = live[u] ? acc[u][j][i] : 0;
         __syncthreads();
         if (owner) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) y32 = __builtin_fmaf((float)accs[i][oj][oreg][ol], sc[i], y32);
+            for (int i = 0; i < R; ++i) y32 = __builtin_fmaf((float)accs[i][oj][oreg][ol], sc[i], y32);
         }
         __syncthreads();
     }
@@ -463,7 +476,7 @@ __global__ __launch_bounds__(512) void w4a4_gemv16_kernel(
     }
 }
 
-template <int NB>
+template <int NB, int U>
 int launch_gemv16(const uint8_t *qa, const float *sa, int M, const quota_weights *W, f16 *y, int ldy,
                   const f16 *res, int ldr, hipStream_t st)
 {
@@ -471,7 +484,7 @@ int launch_gemv16(const uint8_t *qa, const float *sa, int M, const quota_weights
     const double Md = M, Nd = W->N, Kd = W->K;
     ProfScope prof(QUOTA_K_GEMM_ROWS16, 2.0 * Md * Nd * Kd,
                    Nd * Kd / 2 + 2.0 * Nd * G + Md * Kd / 2 + 4 * Md + 2.0 * Md * Nd * (res ? 2 : 1), st);
-    w4a4_gemv16_kernel<NB><<<dim3(W->N / (16 * NB)), dim3(512), 0, st>>>(
+    w4a4_gemv16_kernel<NB, U><<<dim3(W->N / (16 * NB)), dim3(512), 0, st>>>(
         qa, sa, M, W->K, G, (const uint4 *)W->packed, (const f16 *)W->scales, W->N, y, ldy, res, ldr);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
@@ -562,8 +575,8 @@ extern "C" int quota_w4a4_gemm(const uint8_t *qa, const float *sa, int M, const 
     if (acc_i32_opt)
         return launch<2, 1, 2, 0, false, true>(QUOTA_K_GEMM_OTHER, qa, sa, M, W, y, ldy, res, ldr, acc_i32_opt, st);
     if (M <= 16)            // the decode step: stream the weights once, groups spread over 8 waves
-        return W->N <= 8192 ? launch_gemv16<1>(qa, sa, M, W, y, ldy, res, ldr, st)
-                            : launch_gemv16<2>(qa, sa, M, W, y, ldy, res, ldr, st);
+        return W->N <= 8192 ? launch_gemv16<1, 2>(qa, sa, M, W, y, ldy, res, ldr, st)
+                            : launch_gemv16<2, 2>(qa, sa, M, W, y, ldy, res, ldr, st);
     switch (choose_tile(M, W->N, W->K, true)) {
     case 0: return launch<2, 2, 3, 0, false, false>(QUOTA_K_GEMM_64X256, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);
     case 1: return launch<2, 1, 4, 2, true, false>(QUOTA_K_GEMM_64X128, qa, sa, M, W, y, ldy, res, ldr, nullptr, st);

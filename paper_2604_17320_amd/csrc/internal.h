@@ -55,6 +55,8 @@ struct quota_qkv_epilogue {
     uint32_t *k_codes, *v_codes;
     f16 *k_scales, *v_scales;
     long code_row_stride, code_row_offset;   // codes / scales of token row m go to row m * stride + offset
+    const int32_t *row_step;                 // optional (device): ... + clamp(*row_step, 0, max_steps - 1)
+    int max_steps;
 };
 int quota_internal_w4a4_gemm_qkv(const uint8_t *qa, const float *sa, int M, const quota_weights *W,
                                  void *y_opt, const quota_qkv_epilogue *qe, hipStream_t st);
@@ -64,6 +66,9 @@ int quota_internal_rope_kv_quant(const void *qkv_f16, int M, int H, int Hkv, int
                                  const float *cosT, const float *sinT, int n_pos, void *q_rot_f16,
                                  void *khat_f16, void *vhat_f16, uint8_t *k_codes, void *k_scales,
                                  uint8_t *v_codes, void *v_scales, hipStream_t st);
+
+// *step_dev += 1 (one thread; capturable)
+int quota_internal_advance_step(int32_t *step_dev, hipStream_t st);
 
 
 // Limits that the kernels behind the layer calls enforce, for the up-front checks of the layer

@@ -108,13 +108,16 @@ static int qkv_rope_kv_quant(const quota_layer *L, const LayerWs &w, int M, cons
     qe.k_codes = (uint32_t *)w.skc; qe.v_codes = (uint32_t *)w.svc;
     qe.k_scales = w.sks; qe.v_scales = w.svs;
     qe.code_row_stride = 1; qe.code_row_offset = 0;
+    qe.row_step = nullptr; qe.max_steps = 1;
     if (append_to) {        // decode: row b is sequence b's new token; its K/V go straight to cache row len
         qe.k_codes = (uint32_t *)append_to->k_codes; qe.v_codes = (uint32_t *)append_to->v_codes;
         qe.k_scales = (f16 *)append_to->k_scales; qe.v_scales = (f16 *)append_to->v_scales;
         qe.code_row_stride = append_to->capacity; qe.code_row_offset = append_to->len;
+        qe.row_step = append_to->step_dev; qe.max_steps = append_to->max_steps;
     }
     int rc = quota_internal_w4a4_gemm_qkv(w.qa, w.sa, M, &L->qkv, want_qkv ? w.qkv : nullptr, &qe, st);
     if (rc != QUOTA_ERR_SHAPE) return rc;
+    if (append_to && append_to->step_dev) return QUOTA_ERR_SHAPE;      // the device-side step needs the fused form
     TRY(quota_w4a4_gemm(w.qa, w.sa, M, &L->qkv, w.qkv, d + 2 * dkv, nullptr, 0, nullptr, st));
     TRY(quota_internal_rope_kv_quant(w.qkv, M, L->H, Hkv, L->dh, pos, L->cosT, L->sinT, L->n_pos, w.q_rot,
                                      w.khat, w.vhat, w.skc, w.sks, w.svc, w.svs, st));
@@ -259,8 +262,12 @@ extern "C" int quota_decode_layer(const quota_layer *L, const void *x_f16, const
     if (!L || !x_f16 || !pos || !cache || !x_out_f16 || !ws) return QUOTA_ERR_NULL;
     TRY(check_layer(L, B, cache));
     const int H = L->H, dh = L->dh, F = L->F, d = H * dh, Hkv = kv_heads(L), dkv = Hkv * dh;
-    if (cache->len + 1 > cache->capacity) return QUOTA_ERR_CAPACITY;
-    if (cache->len + 1 > QUOTA_MAX_DECODE_ROWS) return QUOTA_ERR_SHAPE;
+    const bool stepped = cache->step_dev != nullptr;    // the step count lives on the device (captured loops)
+    if (stepped && cache->max_steps <= 0) return QUOTA_ERR_INVALID_ARG;
+    const int longest = cache->len + (stepped ? cache->max_steps : 1);
+    if (longest > cache->capacity) return QUOTA_ERR_CAPACITY;
+    if (longest > QUOTA_MAX_DECODE_ROWS) return QUOTA_ERR_SHAPE;
+    if (stepped && (d % 128 != 0 || dkv % 128 != 0)) return QUOTA_ERR_SHAPE;   // needs the fused QKV epilogue
 
     hipStream_t st = (hipStream_t)stream;
     LayerWs w = carve(ws, B, 1, H, Hkv, dh, F);
@@ -275,7 +282,7 @@ extern "C" int quota_decode_layer(const quota_layer *L, const void *x_f16, const
     TRY(dump(t->qkv, w.qkv, (size_t)B * (d + 2 * dkv) * 2, st));
     TRY(dump(t->q_rot, w.q_rot, (size_t)B * d * 2, st));
     quota_kv_cache grown = *cache;      // what the attention reads: the row just written included
-    grown.len += 1;
+    if (!stepped) grown.len += 1;       // (with a device-side step the kernel adds step + 1 itself)
     TRY(quota_attention_decode_gqa(w.q_rot, H, &grown, w.o, st));
     TRY(dump(t->o, w.o, (size_t)B * d * 2, st));
     const f16 *o_used = t->inject_o ? (const f16 *)t->inject_o : w.o;
@@ -289,6 +296,6 @@ extern "C" int quota_decode_layer(const quota_layer *L, const void *x_f16, const
     TRY(dump(t->gu, w.gu, (size_t)B * 2 * F * 2, st));
     TRY(quota_silu_mul_quantize_act(w.gu, B, F, w.qa, w.sa, t->z, t->inject_z, st));
     TRY(quota_w4a4_gemm(w.qa, w.sa, B, &L->down, x_out_f16, d, w.x1, d, nullptr, st));
-    cache->len += 1;                    // only now that every step has been enqueued
+    if (!stepped) cache->len += 1;      // only now that every step has been enqueued
     return QUOTA_OK;
 }

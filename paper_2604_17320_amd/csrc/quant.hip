@@ -173,8 +173,7 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
             for (int e = 0; e < 8; ++e) {
                 float f = (float)v[r].h[e];
                 if (WANT_METRICS) {
-                    int code = code_from(rintf(f * inv_raw));
-                    float deq = (float)code * s_raw;
+                    float deq = code_float(code_bits(f * inv_raw)) * s_raw;
                     float rr = deq - f;
                     rs = __builtin_fma((double)rr, (double)rr, rs);
                 }

@@ -21,9 +21,9 @@ __device__ __forceinline__ uint32_t kv_quant8(const float f[8], f16 *sh_out, Pac
     uint32_t word = 0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        int code = code_from(rintf(f[e] * r));
-        word |= (uint32_t)(code & 0xF) << (4 * e);
-        if (xhat) xhat->h[e] = to_f16((float)code * s);
+        const uint32_t cb = code_bits(f[e] * r);
+        word |= (cb & 0xFu) << (4 * e);
+        if (xhat) xhat->h[e] = to_f16(code_float(cb) * s);
     }
     *sh_out = sh;
     return word;

@@ -26,10 +26,10 @@ __device__ __forceinline__ double quantize_cached_row(const Pack16 *v, int nchun
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 float f = (float)v[r].h[e];
-                int code = code_from(rintf(f * inv));
-                word |= (uint32_t)(code & 0xF) << (4 * e);
+                const uint32_t cb = code_bits(f * inv);
+                word |= (cb & 0xFu) << (4 * e);
                 if (WANT_RES) {
-                    float deq = (float)code * s;
+                    float deq = code_float(cb) * s;
                     float rr = deq - f;
                     rs = __builtin_fma((double)rr, (double)rr, rs);     // product exact in fp64
                 }

@@ -155,6 +155,22 @@ class PrefillStack:
         d = self.layers[0].d
         return x_in[: B * N].view(B * N, d), pos_in[: B * N], N, Nv
 
+    def begin_stepped_decode(self, max_steps: int) -> torch.Tensor:
+        """Switches every layer's cache to a device-side step count (for decode loops captured in a HIP
+        graph): decode() then appends at row len + step and leaves the host lengths alone.  Returns
+        the int32 [1] device counter (zeroed); advance it with qb.quota_advance_step between steps."""
+        self.step_dev = torch.zeros(1, dtype=torch.int32, device=_dev())
+        for c in self.caches:
+            c.desc.step_dev, c.desc.max_steps = self.step_dev.data_ptr(), int(max_steps)
+        return self.step_dev
+
+    def end_stepped_decode(self, steps_done: int):
+        """Folds the steps of a stepped decode loop into the host lengths and returns to host-side lengths."""
+        for c in self.caches:
+            c.desc.len += int(steps_done)
+            c.desc.step_dev, c.desc.max_steps = None, 0
+        self.step_dev = None
+
     def decode(self, x: torch.Tensor, pos: torch.Tensor, taps: Optional[List] = None):
         """One decode step through every layer for one new token per sequence: x fp16 [B, d],
         pos int32 [B] (original position ids).  Each layer appends the token's 4-bit K/V to its own

@@ -163,3 +163,56 @@ def test_stack_prunes_at_candidate_layers_only(qb):
             assert np.all(got_sc == -7.0)
         else:
             assert np.array_equal(got_sc, o["score"])
+
+
+def test_stack_decode_loop_in_a_hip_graph(qb):
+    """A decode loop captured once and replayed: the cache length lives on the device (step count read
+    by the kernels), the new token's input and position are refreshed in place between replays.
+    Every replay must give the bits of the eager step with host-side lengths, appended rows included."""
+    budgets = [64, 30, 12]
+    B, steps = 2, 4
+    shape, Ws, stack, cos, sin = small_stack(3, B, budgets, decode_capacity=steps + 1)
+    x, pos = dev(wl.hidden_state(shape, 6)), dev(wl.positions(shape))
+    stack.run(x, pos)
+    torch.cuda.synchronize()
+    base_len = [c.len for c in stack.caches]
+    r = wl.rng(6, "graph-decode")
+    xs = [dev(r.standard_normal((B, shape.d)).astype(np.float16)) for _ in range(steps)]
+    # eager reference with host-side lengths
+    want = []
+    for i in range(steps):
+        pn = torch.full((B,), shape.N + i, dtype=torch.int32, device="cuda")
+        want.append(stack.decode(xs[i], pn).clone())
+    torch.cuda.synchronize()
+    want_k = [c.k_codes.clone() for c in stack.caches]
+    want_s = [c.v_scales.clone() for c in stack.caches]
+    # rewind, clear the appended rows, and run the same steps as replays of one captured step
+    for c, n in zip(stack.caches, base_len):
+        c.desc.len = n
+        c.k_codes[:, n:].zero_()
+        c.v_scales[:, n:].zero_()
+    step_dev = stack.begin_stepped_decode(steps)
+    x_in = torch.zeros((B, shape.d), dtype=torch.float16, device="cuda")
+    pn = torch.full((B,), shape.N, dtype=torch.int32, device="cuda")
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        stack.decode(x_in, pn)                     # warm-up on the capture stream (writes row base_len: rewritten below)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        y = stack.decode(x_in, pn)
+        qb.quota_advance_step(step_dev)
+        pn.add_(1)
+    step_dev.zero_()
+    pn.fill_(shape.N)
+    for i in range(steps):
+        x_in.copy_(xs[i])
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, want[i]), i
+        assert int(step_dev.item()) == i + 1
+    stack.end_stepped_decode(steps)
+    for c, n, wk, ws_ in zip(stack.caches, base_len, want_k, want_s):
+        assert c.len == n + steps
+        assert torch.equal(c.k_codes[:, : n + steps], wk[:, : n + steps])
+        assert torch.equal(c.v_scales[:, : n + steps], ws_[:, : n + steps])
