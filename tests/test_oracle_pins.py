@@ -754,3 +754,144 @@ def test_layer_wiring_against_an_independent_fp64_block():
     assert not np.all(np.abs((x1f - add_o) - out["h1"].astype(np.float64)) <= tol(x1f))
     assert not np.all(np.abs((xnf - add_d) - xf) <= tol(xnf))
     assert not np.all(np.abs((xnf - add_d) - out["h2"].astype(np.float64)) <= tol(xnf))
+
+
+# ------------------------------------------------ sensitivity profiling (Eq. 1 inputs)
+def _profiler_case(seed, B=2, d=128, H=4, Hkv=2, dh=32, F=192, N=24, scale=0.08):
+    from oracle import profiler
+    r = R(seed)
+    x = (r.standard_normal((B * N, d)) * r.uniform(0.5, 3.0, (B * N, 1))).astype(np.float16)
+    pos = np.tile(5 + 3 * np.arange(N), B).astype(np.int32)
+    dq = (H + 2 * Hkv) * dh
+    W = profiler.FullPrecisionWeights(
+        qkv=(r.standard_normal((dq, d)) * scale).astype(np.float16), o=(r.standard_normal((d, d)) * scale).astype(np.float16),
+        gu=(r.standard_normal((2 * F, d)) * scale).astype(np.float16), down=(r.standard_normal((d, F)) * scale).astype(np.float16),
+        gamma1=r.uniform(0.5, 1.5, d).astype(np.float32), gamma2=r.uniform(0.5, 1.5, d).astype(np.float32),
+        eps=1e-5, H=H, dh=dh, F=F, Hkv=Hkv)
+    cos, sin = wl.rope_tables(dh, int(pos.max()) + 100)
+    return profiler, W, x, pos, B, N, cos, sin
+
+
+def test_full_precision_block_against_torch_library_ops():
+    """The quantizer-free block of the profiler, rebuilt from torch's own routines (rms_norm, linear,
+    scaled_dot_product_attention with is_causal and grouped heads, silu) in fp64; RoPE has no library
+    routine and is pinned by the tests below, so here every position id is 0 (the identity rotation)."""
+    profiler, W, x, pos, B, N, cos, sin = _profiler_case(3)
+    F_ = torch.nn.functional
+    got = profiler.block_full_precision(W, x, np.zeros_like(pos), B, N, cos, sin)
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    d, H, Hkv, dh = W.H * W.dh, W.H, W.Hkv, W.dh
+    xt = t(x).reshape(B, N, d)
+    qkv = F_.linear(F_.rms_norm(xt, (d,), t(W.gamma1), W.eps), t(W.qkv))
+    q = qkv[..., :d].reshape(B, N, H, dh).transpose(1, 2)
+    k = qkv[..., d:d + Hkv * dh].reshape(B, N, Hkv, dh).transpose(1, 2)
+    v = qkv[..., d + Hkv * dh:].reshape(B, N, Hkv, dh).transpose(1, 2)
+    o = F_.scaled_dot_product_attention(q, k, v, is_causal=True, enable_gqa=True).transpose(1, 2).reshape(B, N, d)
+    x1 = xt + F_.linear(o, t(W.o))
+    gu = F_.linear(F_.rms_norm(x1, (d,), t(W.gamma2), W.eps), t(W.gu))
+    want = x1 + F_.linear(F_.silu(gu[..., :W.F]) * gu[..., W.F:], t(W.down))
+    assert np.allclose(got, want.reshape(B * N, d).numpy(), rtol=1e-10, atol=1e-10)
+    # grouped heads matter in this case: reading K/V head h instead of h // (H/Hkv) would differ
+    assert W.H != W.Hkv
+
+
+def test_full_precision_block_rope_and_masking_properties():
+    """What fixes the rotation and the mask inside the block: attention sees only position
+    DIFFERENCES (shifting every id by a constant changes nothing, stretching them does), a token
+    never sees a later one, and the samples of a batch do not mix."""
+    profiler, W, x, pos, B, N, cos, sin = _profiler_case(4)
+    base = profiler.block_full_precision(W, x, pos, B, N, cos, sin)
+    shifted = profiler.block_full_precision(W, x, pos + 17, B, N, cos, sin)
+    assert np.allclose(base, shifted, rtol=0, atol=2e-5)   # the cos/sin tables are fp32
+    stretched = profiler.block_full_precision(W, x, (pos - 5) * 2, B, N, cos, sin)
+    assert np.abs(base - stretched).max() > 1e-3
+    # the rotation acts on q and k only: with every id 0 and one token per sequence the block is
+    # position-free, with two tokens the second one's output depends on its distance to the first
+    x2 = x.copy()
+    x2[N - 1] += 1.0                                    # last token of sample 0
+    pert = profiler.block_full_precision(W, x2, pos, B, N, cos, sin)
+    assert np.array_equal(pert[:N - 1], base[:N - 1])   # causal: earlier tokens unchanged
+    assert np.abs(pert[N - 1] - base[N - 1]).max() > 1e-2
+    assert np.array_equal(pert[N:], base[N:])           # the other sample unchanged
+    x3 = x.copy()
+    x3[0] += 1.0                                        # first token: every later one of its sample moves
+    pert = profiler.block_full_precision(W, x3, pos, B, N, cos, sin).reshape(B, N, -1)
+    assert np.all(np.abs(pert[0] - base.reshape(B, N, -1)[0]).max(axis=1) > 1e-6)
+
+
+def test_full_precision_block_rotation_against_complex_multiplication():
+    """Rotate-half RoPE is multiplication of (x_i + j x_{i+dh/2}) by exp(j pos theta_i): a single
+    head, single token block cannot show it (softmax over one key), so check the q.k logits the
+    block must produce through a 2-token sequence whose value vectors make the output read off the
+    attention weight."""
+    from oracle import profiler
+    r = R(9)
+    dh, P = 32, 64
+    cos, sin = wl.rope_tables(dh, P)
+    t = r.standard_normal((3, dh))
+    pos = np.array([3, 11, 40])
+    got = profiler._rotate(t.copy(), 1, dh, cos[pos].astype(np.float64), sin[pos].astype(np.float64))
+    inv = 1.0e4 ** (-np.arange(0, dh, 2) / dh)
+    z = (t[:, :dh // 2] + 1j * t[:, dh // 2:]) * np.exp(1j * pos[:, None] * inv[None, :])
+    want = np.concatenate([z.real, z.imag], axis=1)
+    assert np.allclose(got, want, rtol=0, atol=1e-6)    # the tables are fp32
+
+
+def test_full_precision_block_closed_forms():
+    """Zero projections: with W_o = 0 and W_down = 0 the block is the identity (both residuals start
+    from the right tensor); with only W_down = 0 the output is x + o W_o^T, and a constant value
+    projection makes o that constant whatever the attention weights are."""
+    profiler, W, x, pos, B, N, cos, sin = _profiler_case(5)
+    import dataclasses
+    xf = x.astype(np.float64)
+    Z = dataclasses.replace(W, o=np.zeros_like(W.o), down=np.zeros_like(W.down))
+    assert np.array_equal(profiler.block_full_precision(Z, x, pos, B, N, cos, sin), xf)
+    # v rows of the qkv weight chosen so that v = c for every token: needs h @ Wv^T = c; use one
+    # token per sequence (N = 1), where attention is the identity on v whatever q and k are
+    one = dataclasses.replace(W, down=np.zeros_like(W.down))
+    got = profiler.block_full_precision(one, x[:B], pos[:B], B, 1, cos, sin)
+    d, dkv = W.H * W.dh, W.Hkv * W.dh
+    g1 = W.gamma1.astype(np.float64)
+    h = xf[:B] / np.sqrt((xf[:B] ** 2).mean(axis=1, keepdims=True) + W.eps) * g1
+    v = h @ W.qkv.astype(np.float64)[d + dkv:].T                         # [B, dkv]
+    o = np.repeat(v.reshape(B, W.Hkv, W.dh), W.H // W.Hkv, axis=1).reshape(B, d)
+    assert np.allclose(got, xf[:B] + o @ W.o.astype(np.float64).T, rtol=1e-12, atol=1e-12)
+
+
+def test_activation_deviation_and_profile():
+    """Eq. 1's two norms against numpy's norm, per sample; and the profile itself: identical runs
+    give S = 0, the low-bit run of the pinned layer composite against the full-precision block
+    gives a deviation of int4 size, and putting the weights on their int4 grid (so that only the
+    activation and K/V quantizers remain) lowers it."""
+    profiler, W, x, pos, B, N, cos, sin = _profiler_case(6, B=3)
+    r = R(10)
+    a, b = r.standard_normal((B * N, 16)), r.standard_normal((B * N, 16))
+    dn, rn = profiler.activation_deviation(a, b, B)
+    for i in range(B):
+        sl = slice(i * N, (i + 1) * N)
+        assert math.isclose(dn[i], np.linalg.norm((a - b)[sl]), rel_tol=1e-12)
+        assert math.isclose(rn[i], np.linalg.norm(b[sl]), rel_tol=1e-12)
+    dn, rn = profiler.activation_deviation(b, b, B)
+    assert np.all(dn == 0) and oracle.recipe.sensitivity(dn, rn, 1e-6) == 0.0
+    dn, _ = profiler.activation_deviation(3.0 * b, b, B)                  # x^q = 3x: ratio exactly 2
+    assert np.allclose(dn / rn, 2.0, rtol=1e-12)
+
+    def quantized(Wf):
+        q = {k_: oracle.quantize_weights(np.asarray(getattr(Wf, k_), np.float32)) for k_ in ("qkv", "o", "gu", "down")}
+        return oracle.LayerWeights(qkv=q["qkv"], o=q["o"], gu=q["gu"], down=q["down"], gamma1=Wf.gamma1,
+                                   gamma2=Wf.gamma2, eps=Wf.eps, H=Wf.H, dh=Wf.dh, F=Wf.F, Hkv=Wf.Hkv), q
+
+    Wq, q = quantized(W)
+    S_full = profiler.profile_sensitivity(Wq, W, x, pos, B, N, 0, N - 4, cos, sin)
+    import dataclasses
+    deq = {k_: (c.astype(np.float64) * np.repeat(s_.astype(np.float64), 128, axis=1)[:, :c.shape[1]]) for k_, (c, s_) in q.items()}
+    on_grid = dataclasses.replace(W, **deq)
+    S_act = profiler.profile_sensitivity(Wq, on_grid, x, pos, B, N, 0, N - 4, cos, sin)
+    print("S with fp weights", S_full, " S with weights on the int4 grid", S_act)
+    assert 0.0 < S_act < S_full < 0.5
+    # the same number from its parts
+    low = oracle.prefill_layer(Wq, x, pos, B, N, 0, N - 4, N - 4, cos, sin)["x_next"].astype(np.float64)
+    full = profiler.block_full_precision(W, x, pos, B, N, cos, sin)
+    ratios = [np.linalg.norm(low[i * N:(i + 1) * N] - full[i * N:(i + 1) * N]) / (np.linalg.norm(full[i * N:(i + 1) * N]) + 1e-6)
+              for i in range(B)]
+    assert math.isclose(S_full, float(np.median(ratios)), rel_tol=1e-12)
