@@ -384,6 +384,62 @@ int quota_make_recipe(const double *S, int m, double tau, double p_min, int V0,
 int quota_gflops_ratio(const int32_t *V_hat, int L, int V0, int T, int d, int F,
                        double F_vt, double F_pj, double *ratio_percent);
 
+/* ---- sensitivity profiling for Eq. 1 (calibration time; DEVICE pointers) ---- */
+
+/* The full-precision counterpart of quota_layer: the same decoder block with
+ * fp16 weights, row-major [N_out][K], same row orders (q | k | v, gate | up),
+ * and no quantizer anywhere.  Hkv = 0 means H. */
+typedef struct quota_fp_layer {
+    int H, dh, F, Hkv;
+    float eps;
+    const float *gamma1, *gamma2;   /* fp32 [d]                               */
+    const void *wqkv;               /* fp16 [d + 2*Hkv*dh][d]                 */
+    const void *wo;                 /* fp16 [d][d]                            */
+    const void *wgu;                /* fp16 [2F][d]                           */
+    const void *wdown;              /* fp16 [d][F]                            */
+    const float *cosT, *sinT;       /* fp32 [n_pos][dh/2]                     */
+    int n_pos;
+} quota_fp_layer;
+
+size_t quota_fp_block_workspace_bytes(const quota_fp_layer *L, int B, int N);
+
+/* The full-precision activation x_l of Eq. 1: one decoder block (RMSNorm,
+ * q|k|v projection, rotate-half RoPE at pos, causal softmax attention with
+ * grouped K/V heads, output projection + residual, RMSNorm, SwiGLU, +
+ * residual) on x fp16 [B][N][d], fp16 storage between the steps, fp32
+ * accumulation, nothing quantized.  x_out fp16 [B][N][d].  Calibration-time
+ * code, not tuned.  ws: quota_fp_block_workspace_bytes bytes.
+ * QUOTA_ERR_SHAPE for dh not 64 / 128, H % Hkv != 0, F % 32 != 0. */
+int quota_fp_block(const quota_fp_layer *L, const void *x_f16, const int32_t *pos,
+                   int B, int N, void *x_out_f16, void *ws, void *stream);
+
+/* Numerator and denominator of Eq. 1 for each of B samples: diff_norm[b] =
+ * ||x^q_b - x_b||_2, ref_norm[b] = ||x_b||_2 over the n_per_sample fp16 values
+ * of sample b (all its tokens and channels), accumulated in fp64.  xq, x fp16
+ * [B][n_per_sample]; diff_norm, ref_norm fp64 [B] (device).  Copy them to the
+ * host for quota_sensitivity. */
+int quota_activation_deviation(const void *xq_f16, const void *x_f16, int B,
+                               long n_per_sample, double *diff_norm,
+                               double *ref_norm, void *stream);
+
+size_t quota_profile_block_workspace_bytes(const quota_layer *Lq, const quota_fp_layer *Lf,
+                                           int B, int N);
+
+/* Eq. 1's measurement for one block and B calibration samples: runs the
+ * deployed low-bit block (quota_prefill_layer with QUOTA_KEEP_ALL: calibration
+ * precedes the recipe, nothing is pruned) and the full-precision block on the
+ * same input x / pos, and returns the per-sample norms of the difference and
+ * of the full-precision output (device fp64 [B]).  Both runs start from the
+ * same block input, so the deviation is this block's own.  scratch_cache: a
+ * cache descriptor of this layer's geometry with room for N more rows; its
+ * rows beyond len are overwritten and len is left as it came.
+ * ws: quota_profile_block_workspace_bytes bytes.  Errors as the two block
+ * calls; QUOTA_ERR_SHAPE when the two layers' geometries differ. */
+int quota_profile_block(const quota_layer *Lq, const quota_fp_layer *Lf,
+                        const void *x_f16, const int32_t *pos, int B, int N,
+                        quota_kv_cache *scratch_cache, double *diff_norm,
+                        double *ref_norm, void *ws, void *stream);
+
 /* ---- decode over the pruned 4-bit KV cache ------------------------------- */
 
 /* Single-query attention of one new token per sequence over `cache` (deployment

@@ -48,6 +48,13 @@ class Layer(C.Structure):
                 ("cosT", C.c_void_p), ("sinT", C.c_void_p), ("n_pos", C.c_int), ("Hkv", C.c_int)]
 
 
+class FpLayer(C.Structure):
+    _fields_ = [("H", C.c_int), ("dh", C.c_int), ("F", C.c_int), ("Hkv", C.c_int), ("eps", C.c_float),
+                ("gamma1", C.c_void_p), ("gamma2", C.c_void_p), ("wqkv", C.c_void_p), ("wo", C.c_void_p),
+                ("wgu", C.c_void_p), ("wdown", C.c_void_p), ("cosT", C.c_void_p), ("sinT", C.c_void_p),
+                ("n_pos", C.c_int)]
+
+
 class State(C.Structure):
     _fields_ = [("B", C.c_int), ("N", C.c_int), ("vis_begin", C.c_int), ("Nv", C.c_int),
                 ("x", C.c_void_p), ("pos", C.c_void_p), ("x_out", C.c_void_p), ("pos_out", C.c_void_p)]
@@ -80,7 +87,8 @@ def lib() -> C.CDLL:
         L.quota_kernel_name.restype = C.c_char_p
         for name in ["quota_weights_packed_bytes", "quota_weights_scale_bytes",
                      "quota_attention_workspace_bytes", "quota_prefill_workspace_bytes",
-                     "quota_decode_workspace_bytes"]:
+                     "quota_decode_workspace_bytes", "quota_fp_block_workspace_bytes",
+                     "quota_profile_block_workspace_bytes"]:
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -262,6 +270,32 @@ def quota_gflops_ratio(V_hat, V0: int, T: int, d: int, F: int, F_vt: float = 0.0
     _check(lib().quota_gflops_ratio(v, L, int(V0), int(T), int(d), int(F), C.c_double(F_vt), C.c_double(F_pj),
                                     C.byref(out)), "quota_gflops_ratio")
     return out.value
+
+
+def quota_fp_block_workspace_bytes(L: FpLayer, B, N):
+    return lib().quota_fp_block_workspace_bytes(C.byref(L), int(B), int(N))
+
+
+def quota_fp_block(L: FpLayer, x, pos, B, N, x_out, ws):
+    _check(lib().quota_fp_block(C.byref(L), _ptr(x, torch.float16), _ptr(pos, torch.int32), int(B), int(N),
+                                _ptr(x_out, torch.float16), _ptr(ws), _stream()), "quota_fp_block")
+
+
+def quota_activation_deviation(xq, x, B, n_per_sample, diff_norm, ref_norm):
+    _check(lib().quota_activation_deviation(_ptr(xq, torch.float16), _ptr(x, torch.float16), int(B),
+                                            C.c_long(n_per_sample), _ptr(diff_norm, torch.float64),
+                                            _ptr(ref_norm, torch.float64), _stream()),
+           "quota_activation_deviation")
+
+
+def quota_profile_block_workspace_bytes(Lq: Layer, Lf: FpLayer, B, N):
+    return lib().quota_profile_block_workspace_bytes(C.byref(Lq), C.byref(Lf), int(B), int(N))
+
+
+def quota_profile_block(Lq: Layer, Lf: FpLayer, x, pos, B, N, scratch_cache: KVCache, diff_norm, ref_norm, ws):
+    _check(lib().quota_profile_block(C.byref(Lq), C.byref(Lf), _ptr(x, torch.float16), _ptr(pos, torch.int32),
+                                     int(B), int(N), C.byref(scratch_cache), _ptr(diff_norm, torch.float64),
+                                     _ptr(ref_norm, torch.float64), _ptr(ws), _stream()), "quota_profile_block")
 
 
 def quota_attention_decode(q, cache: KVCache, o):

@@ -100,6 +100,40 @@ class PrefillLayer:
         return sum(w.nbytes() for w in (self.qkv, self.o, self.gu, self.down))
 
 
+class FullPrecisionLayer:
+    """fp16 weights of one decoder layer for the calibration-time full-precision block (Eq. 1)."""
+
+    def __init__(self, H: int, dh: int, F: int, wqkv: torch.Tensor, wo: torch.Tensor, wgu: torch.Tensor,
+                 wdown: torch.Tensor, gamma1: torch.Tensor, gamma2: torch.Tensor, eps: float,
+                 cosT: torch.Tensor, sinT: torch.Tensor, Hkv: Optional[int] = None):
+        self.H, self.dh, self.F, self.d = H, dh, F, H * dh
+        self.Hkv = H if Hkv is None else Hkv
+        self.w = [t.to(torch.float16).contiguous() for t in (wqkv, wo, wgu, wdown)]
+        self.gamma1, self.gamma2, self.cosT, self.sinT = gamma1, gamma2, cosT, sinT
+        self.desc = qb.FpLayer(H, dh, F, self.Hkv, eps, gamma1.data_ptr(), gamma2.data_ptr(),
+                               *[t.data_ptr() for t in self.w], cosT.data_ptr(), sinT.data_ptr(), cosT.shape[0])
+
+    def forward(self, x: torch.Tensor, pos: torch.Tensor, B: int, N: int) -> torch.Tensor:
+        ws = torch.empty(qb.quota_fp_block_workspace_bytes(self.desc, B, N), dtype=torch.uint8, device=x.device)
+        out = torch.empty_like(x)
+        qb.quota_fp_block(self.desc, x, pos, B, N, out, ws)
+        return out
+
+
+def profile_sensitivity(layer: PrefillLayer, full: FullPrecisionLayer, x: torch.Tensor, pos: torch.Tensor,
+                        B: int, N: int, eta: float = 1e-6):
+    """S of Eq. 1 for one block over the B calibration samples in x (fp16 [B*N, d]): the low-bit and
+    the full-precision block run on the same input; returns (S, diff_norm, ref_norm)."""
+    dev = x.device
+    scratch = KVCache4(B, N, layer.Hkv, layer.dh)
+    ws = torch.empty(qb.quota_profile_block_workspace_bytes(layer.desc, full.desc, B, N), dtype=torch.uint8, device=dev)
+    dn = torch.empty(B, dtype=torch.float64, device=dev)
+    rn = torch.empty(B, dtype=torch.float64, device=dev)
+    qb.quota_profile_block(layer.desc, full.desc, x, pos, B, N, scratch.desc, dn, rn, ws)
+    dn, rn = dn.cpu().tolist(), rn.cpu().tolist()
+    return qb.quota_sensitivity(dn, rn, eta), dn, rn
+
+
 def make_taps(**tensors) -> qb.Taps:
     t = qb.Taps()
     for k, v in tensors.items():
