@@ -44,20 +44,22 @@ __global__ __launch_bounds__(256) void kv_append_rows_kernel(
 }
 
 // One workgroup per (K/V head, sequence); it serves the `rep` query heads that share the K/V head,
-// RC at a time, so a K/V row is fetched from HBM once per group of query heads.  The cached rows
-// are walked in tiles of DEC_TILE tokens with a running softmax (maximum, sum, rescaled output), so
-// the scores of one tile are all the LDS the kernel needs, whatever the cache length.
-//   scores:  DH/32 lanes per token, each loads 16 contiguous bytes of the token's K codes (32
+// RC at a time (1 when every query head has its own K/V head, else 2), so a K/V row is fetched
+// from HBM once per group of query heads.  The cached rows are walked in tiles of DEC_TILE tokens
+// with a running softmax (maximum, sum, rescaled output), so the scores of one tile are all the
+// LDS the kernel needs, whatever the cache length.
+//   loads:   the walk is latency-bound (a workgroup owns a few tens of KB), so every K and V load
+//            of a tile is issued before the first use: UN passes of 256 lanes x 16 bytes each;
+//   scores:  DH/32 lanes per token, each holds 16 contiguous bytes of the token's K codes (32
 //            channels) -- a wave reads whole 64- or 32-byte row segments -- dequantizes them as
 //            packed fp16 pairs and dots them with the query; the lanes of a token add up by shuffles;
 //   output:  the same lanes own 32 channels of V each and accumulate p * v_hat over their share of
 //            the tokens; the token lanes are summed through LDS in a fixed order at the end.
 // step_dev (optional): the cache length is len + *step_dev (a HIP-graph-captured decode loop keeps
 // its step count on the device).
-constexpr int DEC_TILE = 1024;
-constexpr int DEC_RC = 2;           // query heads served per pass over the K/V rows
+constexpr int DEC_TILE = 512;
 
-template <int DH>
+template <int DH, int RC>
 __global__ __launch_bounds__(256) void decode_attention_kernel(
     const f16 *__restrict__ q, int d, int dkv, int rep, const uint32_t *__restrict__ kc,
     const f16 *__restrict__ ks, const uint32_t *__restrict__ vc, const f16 *__restrict__ vs, int capacity,
@@ -65,33 +67,40 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
 {
     constexpr int PPT = DH / 32;            // 16-byte pieces (lanes) per token and head
     constexpr int TP = 256 / PPT;           // tokens per pass of the workgroup
+    constexpr int UN = DEC_TILE / TP;       // passes per tile
     constexpr int WPT = DH / 8;             // packed dwords per token and head
     constexpr int GPT = DH / 64;            // scale groups per token and head
-    __shared__ h2 qp[DEC_RC][DH / 2];       // q as pairs: qp[r][4 i + e] = (q[8 i + e], q[8 i + e + 4])
-    __shared__ float sc[DEC_RC][DEC_TILE];
-    __shared__ float red[TP * 32 * PPT / 2];          // one half of the token lanes at a time
-    __shared__ float wred[2][DEC_RC][4];
+    __shared__ h2 qp[RC][DH / 2];           // q as pairs: qp[r][4 i + e] = (q[8 i + e], q[8 i + e + 4])
+    __shared__ float sc[RC][DEC_TILE];
+    __shared__ float red[32 * (128 + 1)];   // one half of the token lanes at a time: [32 channels][128 lanes], padded
+    __shared__ float wred[2][RC][4];
     const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, wave = tid >> 6;
     const int piece = tid % PPT, tl = tid / PPT;
+    const int wave_t0 = (tid & ~63) / PPT;  // first token of this wave within a pass
     const int n32 = dkv >> 3, ng = dkv >> 6;
     int L = len;
     if (step_dev) L += min(max(*step_dev, 0), max_steps - 1) + 1;      // the row this step appended included
     const float scale = 1.0f / sqrtf((float)DH);
     const size_t row0 = (size_t)b * capacity;
 
-    for (int r0 = 0; r0 < rep; r0 += DEC_RC) {
-        const int nr = min(DEC_RC, rep - r0);
+    for (int r0 = 0; r0 < rep; r0 += RC) {
+        const int nr = min(RC, rep - r0);
         __syncthreads();                    // qp, sc, red of the previous pass are done with
-        if (tid < DEC_RC * (DH / 2)) {
+        if (tid < RC * (DH / 2)) {
             const int r = tid / (DH / 2), i = tid % (DH / 2);
             const int hq = min(h * rep + r0 + r, h * rep + rep - 1);
             const f16 *qh = q + (size_t)b * d + hq * DH + 8 * (i >> 2) + (i & 3);
             qp[r][i] = h2{qh[0], qh[4]};
         }
         __syncthreads();
-        float m_run[DEC_RC], l_run[DEC_RC], acc[DEC_RC][32];
+        h2 qr[RC][16];                      // this lane's 32 channels of each query, as pairs
 #pragma unroll
-        for (int r = 0; r < DEC_RC; ++r) {
+        for (int r = 0; r < RC; ++r)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) qr[r][i] = qp[r][16 * piece + i];
+        float m_run[RC], l_run[RC], acc[RC][32];
+#pragma unroll
+        for (int r = 0; r < RC; ++r) {
             m_run[r] = -INFINITY;
             l_run[r] = 0.0f;
 #pragma unroll
@@ -99,34 +108,51 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
         }
         for (int t0 = 0; t0 < L; t0 += DEC_TILE) {
             const int tn = min(DEC_TILE, L - t0);
+            uint4 kq[UN], vq[UN];
+            _Float16 ksc[UN], vsc[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int t = u * TP + tl;
+                const size_t row = row0 + t0 + (t < tn ? t : 0);
+                kq[u] = *reinterpret_cast<const uint4 *>(kc + row * n32 + h * WPT + 4 * piece);
+                ksc[u] = ks[row * ng + h * GPT + (piece >> 1)];
+            }
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int t = u * TP + tl;
+                const size_t row = row0 + t0 + (t < tn ? t : 0);
+                vq[u] = *reinterpret_cast<const uint4 *>(vc + row * n32 + h * WPT + 4 * piece);
+                vsc[u] = vs[row * ng + h * GPT + (piece >> 1)];
+            }
             // ---- scores of the tile
-            float mx[DEC_RC];
+            float mx[RC];
 #pragma unroll
-            for (int r = 0; r < DEC_RC; ++r) mx[r] = -INFINITY;
-            for (int tb = 0; tb < tn; tb += TP) {
-                const int t = tb + tl;
+            for (int r = 0; r < RC; ++r) mx[r] = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                if (u * TP + wave_t0 >= tn) continue;       // the whole wave is past the end
+                const int t = u * TP + tl;
                 const bool ok = t < tn;
-                const size_t row = row0 + t0 + (ok ? t : 0);
-                const uint4 pk = *reinterpret_cast<const uint4 *>(kc + row * n32 + h * WPT + 4 * piece);
-                const _Float16 sh = ks[row * ng + h * GPT + (piece >> 1)];
-                const h2 s2 = h2{sh, sh};
-                const uint32_t ww[4] = {pk.x ^ 0x88888888u, pk.y ^ 0x88888888u, pk.z ^ 0x88888888u,
-                                        pk.w ^ 0x88888888u};
-                float dot[DEC_RC];
+                const h2 s2 = h2{ksc[u], ksc[u]};
+                const uint32_t ww[4] = {kq[u].x ^ 0x88888888u, kq[u].y ^ 0x88888888u, kq[u].z ^ 0x88888888u,
+                                        kq[u].w ^ 0x88888888u};
+                float dot[RC][4];           // four independent chains: the dot instruction accumulates in place
 #pragma unroll
-                for (int r = 0; r < DEC_RC; ++r) dot[r] = 0.0f;
+                for (int r = 0; r < RC; ++r)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                    for (int i = 0; i < 4; ++i) dot[r][i] = 0.0f;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {       // channels (8 id + e, 8 id + e + 4), id = 4 piece + i
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {       // channels (8 id + e, 8 id + e + 4), id = 4 piece + i
                         const h2 kh = dequant_pair(ww[i], e, s2);
 #pragma unroll
-                        for (int r = 0; r < DEC_RC; ++r)
-                            dot[r] = __builtin_amdgcn_fdot2(qp[r][4 * (4 * piece + i) + e], kh, dot[r], false);
+                        for (int r = 0; r < RC; ++r)
+                            dot[r][i] = __builtin_amdgcn_fdot2(qr[r][4 * i + e], kh, dot[r][i], false);
                     }
 #pragma unroll
-                for (int r = 0; r < DEC_RC; ++r) {
-                    float v = dot[r];
+                for (int r = 0; r < RC; ++r) {
+                    float v = (dot[r][0] + dot[r][1]) + (dot[r][2] + dot[r][3]);
                     v += __shfl_xor(v, 1, 64);
                     if (PPT == 4) v += __shfl_xor(v, 2, 64);
                     v *= scale;
@@ -135,14 +161,14 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
                 }
             }
 #pragma unroll
-            for (int r = 0; r < DEC_RC; ++r) {
+            for (int r = 0; r < RC; ++r) {
                 mx[r] = wave_max(mx[r]);
                 if ((tid & 63) == 0) wred[0][r][wave] = mx[r];
             }
             __syncthreads();                // scores and wave maxima visible
-            float alpha[DEC_RC], m_new[DEC_RC], sum[DEC_RC];
+            float alpha[RC], m_new[RC], sum[RC];
 #pragma unroll
-            for (int r = 0; r < DEC_RC; ++r) {
+            for (int r = 0; r < RC; ++r) {
                 const float tm = fmaxf(fmaxf(wred[0][r][0], wred[0][r][1]), fmaxf(wred[0][r][2], wred[0][r][3]));
                 m_new[r] = fmaxf(m_run[r], tm);
                 alpha[r] = __expf(m_run[r] - m_new[r]);      // 0 on the first tile
@@ -158,31 +184,30 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
             }
             __syncthreads();                // probabilities and wave sums visible
 #pragma unroll
-            for (int r = 0; r < DEC_RC; ++r) {
+            for (int r = 0; r < RC; ++r) {
                 l_run[r] = l_run[r] * alpha[r] + (((wred[1][r][0] + wred[1][r][1]) + wred[1][r][2]) + wred[1][r][3]);
 #pragma unroll
                 for (int e = 0; e < 32; ++e) acc[r][e] *= alpha[r];
             }
             // ---- p * v_hat of the tile
-            for (int tb = 0; tb < tn; tb += TP) {
-                const int t = tb + tl;
-                const bool ok = t < tn;
-                const size_t row = row0 + t0 + (ok ? t : 0);
-                const uint4 pk = *reinterpret_cast<const uint4 *>(vc + row * n32 + h * WPT + 4 * piece);
-                const _Float16 sh = vs[row * ng + h * GPT + (piece >> 1)];
-                const h2 s2 = h2{sh, sh};
-                const uint32_t ww[4] = {pk.x ^ 0x88888888u, pk.y ^ 0x88888888u, pk.z ^ 0x88888888u,
-                                        pk.w ^ 0x88888888u};
-                float pv[DEC_RC];
 #pragma unroll
-                for (int r = 0; r < DEC_RC; ++r) pv[r] = ok ? sc[r][t] : 0.0f;
+            for (int u = 0; u < UN; ++u) {
+                if (u * TP + wave_t0 >= tn) continue;
+                const int t = u * TP + tl;
+                const bool ok = t < tn;
+                const h2 s2 = h2{vsc[u], vsc[u]};
+                const uint32_t ww[4] = {vq[u].x ^ 0x88888888u, vq[u].y ^ 0x88888888u, vq[u].z ^ 0x88888888u,
+                                        vq[u].w ^ 0x88888888u};
+                float pv[RC];
+#pragma unroll
+                for (int r = 0; r < RC; ++r) pv[r] = ok ? sc[r][t] : 0.0f;
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const h2 vh = dequant_pair(ww[i], e, s2);
 #pragma unroll
-                        for (int r = 0; r < DEC_RC; ++r) {
+                        for (int r = 0; r < RC; ++r) {
                             acc[r][8 * i + e] = fmaf(pv[r], (float)vh[0], acc[r][8 * i + e]);
                             acc[r][8 * i + e + 4] = fmaf(pv[r], (float)vh[1], acc[r][8 * i + e + 4]);
                         }
@@ -190,20 +215,24 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
             }
             __syncthreads();                // the tile's scores have been consumed
         }
-        // ---- the token lanes meet in LDS, half of them at a time, summed in lane order
-        for (int r = 0; r < nr; ++r) {
+        // ---- the token lanes meet in LDS, half of them at a time, summed in lane order (red is
+        // laid out [channel][token lane] so that the lanes of a wave write consecutive words; the
+        // loop over r is unrolled to keep acc in registers)
+#pragma unroll
+        for (int r = 0; r < RC; ++r) {
+            if (r >= nr) break;
             float out = 0.0f;
             for (int half = 0; half < 2; ++half) {
                 __syncthreads();
                 if (tl / (TP / 2) == half) {
 #pragma unroll
-                    for (int e = 0; e < 32; ++e) red[((tl % (TP / 2)) * PPT + piece) * 32 + e] = acc[r][e];
+                    for (int e = 0; e < 32; ++e) red[e * (128 + 1) + (tl % (TP / 2)) * PPT + piece] = acc[r][e];
                 }
                 __syncthreads();
                 if (tid < DH) {
                     const int pc = tid >> 5, e = tid & 31;
 #pragma unroll 4
-                    for (int i = 0; i < TP / 2; ++i) out += red[(i * PPT + pc) * 32 + e];
+                    for (int i = 0; i < TP / 2; ++i) out += red[e * (128 + 1) + i * PPT + pc];
                 }
             }
             if (tid < DH) o[(size_t)b * d + (h * rep + r0 + r) * DH + tid] = (f16)(out / l_run[r]);
@@ -260,7 +289,8 @@ extern "C" int quota_attention_decode_gqa(const void *q_f16, int Hq, const quota
     const double rows = (double)cache->B * longest;
     ProfScope prof(QUOTA_K_ATTENTION_DECODE, 4.0 * rows * d, rows * (dkv + dkv / 16.0) + 4.0 * cache->B * d, st);
     dim3 grid(cache->H, cache->B), block(256);
-    auto kernel = cache->dh == 128 ? decode_attention_kernel<128> : decode_attention_kernel<64>;
+    auto kernel = cache->dh == 128 ? (rep == 1 ? decode_attention_kernel<128, 1> : decode_attention_kernel<128, 2>)
+                                   : (rep == 1 ? decode_attention_kernel<64, 1> : decode_attention_kernel<64, 2>);
     kernel<<<grid, block, 0, st>>>(
         (const f16 *)q_f16, d, dkv, rep, (const uint32_t *)cache->k_codes, (const f16 *)cache->k_scales,
         (const uint32_t *)cache->v_codes, (const f16 *)cache->v_scales, cache->capacity, cache->len,

@@ -14,6 +14,13 @@ they read for the plain elementwise copy of known size that bench.py ran in the 
 
     python -m paper_2604_17320_amd.profile_summary mfma <sq_counter_collection.csv> [bench.json]
 
+    python -m paper_2604_17320_amd.profile_summary bandwidth <kernel_stats.csv> \
+           <fetch_counter_collection.csv> <write_counter_collection.csv> <copy MiB> <bandwidth.json>
+
+`bandwidth` does the same for a `bench.py --bandwidth-only` run (the bandwidth-bound kernels at the
+batched-serving row count): per kernel the trace's average duration, the HBM bytes the two counter
+passes read per launch, the algorithmic bytes, and the rate against the HBM peak.
+
 `mfma` condenses one `--pmc` pass of SQ counters (SQ_INSTS_MFMA SQ_INSTS_VALU
 SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_ACTIVE_INST_VALU SQ_WAVE_CYCLES SQ_WAIT_INST_ANY
 SQ_WAVES) into one line per GEMM kernel class: MFMA instructions issued per launch and what they
@@ -38,6 +45,7 @@ CLASSES = [
     ("silu_mul_quantize_act_kernel", "silu_mul_quantize_act"),
     ("rmsnorm_quantize_act_kernel", "rmsnorm_quantize_act"),
     ("quantize_act_kernel", "quantize_act"),
+    ("rope_kv_quant_mha_kernel", "rope_kv_quant"),
     ("rope_kv_quant_kernel", "rope_kv_quant"),
     ("kv_quant_append_kernel", "kv_quant_append"),
     ("attn_fwd_kernel", "attention_fwd"),
@@ -131,6 +139,59 @@ def traffic(fetch_csv, write_csv, copy_mib, bench_path=None):
     print(json.dumps(out, indent=1))
 
 
+def bandwidth_case(name):
+    """Kernel symbol -> the case name bench.py's bandwidth_kernels block uses."""
+    cls = classify(name)
+    if cls in ("quantize_act", "rmsnorm_quantize_act") and (cls + "_kernelILb1E") in name:
+        return cls + " (+ m_mag, m_res)"
+    return cls
+
+
+def bandwidth(stats_csv, fetch_csv, write_csv, copy_mib, bench_path):
+    bench = load_bench(bench_path)["bandwidth_kernels"]
+    cases = bench["kernels"]
+    copy_bytes = int(copy_mib) << 20
+    dur = collections.defaultdict(lambda: [0, 0.0])
+    for r in csv.DictReader(open(stats_csv)):
+        c = bandwidth_case(r["Name"])
+        if c in cases:
+            dur[c][0] += int(r["Calls"])
+            dur[c][1] += float(r["TotalDurationNs"])
+    hbm = collections.defaultdict(dict)
+    scales = {}
+    for tag, path, ctr in (("fetch", fetch_csv, "FETCH_SIZE"), ("write", write_csv, "WRITE_SIZE")):
+        vals, copy = collections.defaultdict(list), []
+        for r in csv.DictReader(open(path)):
+            if r["Counter_Name"] != ctr:
+                continue
+            name, v = r["Kernel_Name"], float(r["Counter_Value"])
+            c = bandwidth_case(name)
+            if c in cases:
+                vals[c].append(v)
+            elif "elementwise_kernel" in name and "AUnaryFunctor" in name and int(r["Grid_Size"]) == copy_bytes // 16:
+                copy.append(v)
+        if len(copy) != 1:
+            raise SystemExit(f"expected one calibration copy in {path}, found {len(copy)}")
+        scales[tag] = copy_bytes / (copy[0] * 1024.0)
+        for c, v in vals.items():
+            v = sorted(v)[len(v) // 2:]               # the warm-up launch of a case may differ; upper half
+            hbm[c][tag] = sum(v) / len(v) * 1024.0 * scales[tag]
+    print(f"shape: {bench['shape']}")
+    print(f"counter scale (known-size copy of {copy_mib} MiB): FETCH_SIZE x {scales['fetch']:.4f}, WRITE_SIZE x {scales['write']:.4f}")
+    print(f"{'kernel':40s} {'calls':>5s} {'avg us (trace)':>14s} {'algorithmic MB':>14s} {'HBM fetch MB':>12s} {'HBM write MB':>12s} "
+          f"{'GB/s':>8s} {'of 8 TB/s':>9s} {'events: us':>10s}")
+    for c, k in cases.items():
+        if c not in dur:
+            continue
+        calls, ns = dur[c]
+        us = ns / calls / 1e3
+        alg = k["MB"] * 1e6
+        print(f"{c:40s} {calls:5d} {us:14.2f} {alg / 1e6:14.1f} {hbm[c].get('fetch', float('nan')) / 1e6:12.1f} "
+              f"{hbm[c].get('write', float('nan')) / 1e6:12.1f} {alg / us / 1e3:8.0f} {alg / us / 1e3 / 8000.0:9.3f} {k['avg_us']:10.2f}")
+    print("\nGB/s = algorithmic bytes (inputs once + outputs once, 4-bit data as half bytes) / the trace's average duration;\n"
+          "events: us = what bench.py's own event pair around the same launches read in the plain run.")
+
+
 def mfma(csv_path, bench_path=None):
     bench = load_bench(bench_path)
     per = collections.defaultdict(lambda: collections.defaultdict(list))     # class -> counter -> values
@@ -170,6 +231,8 @@ if __name__ == "__main__":
         stats(*sys.argv[2:4])
     elif len(sys.argv) >= 3 and sys.argv[1] == "mfma":
         mfma(*sys.argv[2:4])
+    elif len(sys.argv) >= 7 and sys.argv[1] == "bandwidth":
+        bandwidth(*sys.argv[2:7])
     elif len(sys.argv) >= 5 and sys.argv[1] == "traffic":
         traffic(*sys.argv[2:6])
     else:
