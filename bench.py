@@ -100,6 +100,8 @@ def bandwidth_kernels(shape, seed, reps=12, with_gemm=False):
     cache = KVCache4(B, n_keep + 66, H, dh)
     dcaches = [KVCache4(B, n_keep + 66, H, dh) for _ in range(12)]      # 12 x 25.5 MB: decode reads rotate too
     for c in dcaches:
+        for t in (c.k_codes, c.v_codes, c.k_scales, c.v_scales):
+            t.zero_()                          # the rows past the appended prefix are read too
         k_, v_ = kv_in[0]
         qb.quota_kv_quant_append(k_, v_, B, N, H, dh, keep, n_keep, c.desc)
         c.desc.len = n_keep + 65               # pruned prefix + 65 decoded tokens
@@ -338,6 +340,8 @@ def main():
     ap.add_argument("--serving-shape", action="store_true",
                     help="also report (outside the timed region) per-kernel rates at the batch-16 serving "
                          "shape and the batch-16 prefill + decode steps on the same weights")
+    ap.add_argument("--no-bandwidth", action="store_true",
+                    help="leave the bandwidth-kernel block out (counter passes over the stack's own launches)")
     ap.add_argument("--bandwidth-only", action="store_true",
                     help="run only the bandwidth-kernel block at the batch-16 row count and print it "
                          "(the run that kernel traces and HBM counters of those kernels are taken from)")
@@ -476,7 +480,8 @@ def main():
                              frac_int8_peak=round(gemm_ops / (gemm_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 4)
                              if gemm_ms else None, step_ms=round(gemm_ms / args.profile_steps, 4)),
                kernels=kern)
-    out["bandwidth_kernels"] = bandwidth_kernels(shape, args.seed, with_gemm=args.serving_shape)
+    if not args.no_bandwidth:
+        out["bandwidth_kernels"] = bandwidth_kernels(shape, args.seed, with_gemm=args.serving_shape)
     if args.serving_shape:
         if args.config == "c3":
             out["serving_decode"] = serving_decode(shape, stack, budgets, args.seed)
