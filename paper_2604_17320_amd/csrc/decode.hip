@@ -5,6 +5,7 @@
 // and sequence (K and V codes plus fp16 scales), a quarter of an fp16 cache.
 #include "common.h"
 #include "internal.h"
+#include "gemm_common.h"
 
 namespace {
 
@@ -43,13 +44,14 @@ __global__ __launch_bounds__(256) void kv_append_rows_kernel(
     }
 }
 
-// One workgroup per (K/V head, sequence); it serves the `rep` query heads that share the K/V head,
-// RC at a time (1 when every query head has its own K/V head, else 2), so a K/V row is fetched
-// from HBM once per group of query heads.  The cached rows are walked in tiles of DEC_TILE tokens
-// with a running softmax (maximum, sum, rescaled output), so the scores of one tile are all the
-// LDS the kernel needs, whatever the cache length.
+// One workgroup per (sequence, K/V head, RC query heads that share the K/V head), XCD-aware order;
+// RC is 1 when every query head has its own K/V head, else 2.  The workgroups of a K/V head are
+// neighbours on one XCD, so its rows come from HBM once and from that XCD's L2 afterwards.  The
+// cached rows are walked in tiles of DEC_TILE tokens with a running softmax (maximum, sum,
+// rescaled output), so the scores of one tile are all the LDS the kernel needs, whatever the
+// cache length.
 //   loads:   the walk is latency-bound (a workgroup owns a few tens of KB), so every K and V load
-//            of a tile is issued before the first use: UN passes of 256 lanes x 16 bytes each;
+//            of a tile is issued before the first use: UN passes of 512 lanes x 16 bytes each;
 //   scores:  DH/32 lanes per token, each holds 16 contiguous bytes of the token's K codes (32
 //            channels) -- a wave reads whole 64- or 32-byte row segments -- dequantizes them as
 //            packed fp16 pairs and dots them with the query; the lanes of a token add up by shuffles;
@@ -58,23 +60,32 @@ __global__ __launch_bounds__(256) void kv_append_rows_kernel(
 // step_dev (optional): the cache length is len + *step_dev (a HIP-graph-captured decode loop keeps
 // its step count on the device).
 constexpr int DEC_TILE = 512;
+constexpr int DEC_THREADS = 512;     // 8 waves: with two workgroups on a CU every SIMD has four waves to interleave
 
 template <int DH, int RC>
-__global__ __launch_bounds__(256) void decode_attention_kernel(
+__global__ __launch_bounds__(DEC_THREADS, RC == 1 ? 4 : 2) void decode_attention_kernel(
     const f16 *__restrict__ q, int d, int dkv, int rep, const uint32_t *__restrict__ kc,
     const f16 *__restrict__ ks, const uint32_t *__restrict__ vc, const f16 *__restrict__ vs, int capacity,
-    int len, const int32_t *__restrict__ step_dev, int max_steps, f16 *__restrict__ o)
+    int len, const int32_t *__restrict__ step_dev, int max_steps, f16 *__restrict__ o, int n_kv_heads)
 {
     constexpr int PPT = DH / 32;            // 16-byte pieces (lanes) per token and head
-    constexpr int TP = 256 / PPT;           // tokens per pass of the workgroup
+    constexpr int TP = DEC_THREADS / PPT;   // tokens per pass of the workgroup
     constexpr int UN = DEC_TILE / TP;       // passes per tile
     constexpr int WPT = DH / 8;             // packed dwords per token and head
     constexpr int GPT = DH / 64;            // scale groups per token and head
     __shared__ h2 qp[RC][DH / 2];           // q as pairs: qp[r][4 i + e] = (q[8 i + e], q[8 i + e + 4])
     __shared__ float sc[RC][DEC_TILE];
-    __shared__ float red[32 * (128 + 1)];   // one half of the token lanes at a time: [32 channels][128 lanes], padded
-    __shared__ float wred[2][RC][4];
-    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, wave = tid >> 6;
+    __shared__ float red[32 * (128 + 1)];   // 128 token lanes at a time: [32 channels][128 lanes], padded
+    constexpr int NW = DEC_THREADS / 64;    // waves
+    constexpr int NQ = DEC_THREADS / 128;   // rounds of the final sum (128 token lanes each)
+    __shared__ float wred[2][RC][NW];
+    // (sequence, head) pairs are dealt to the 8 XCDs in contiguous ranges: the heads of a sequence
+    // share the 128-byte lines of its cache rows (two heads' codes, all heads' scales), and each
+    // XCD has its own L2
+    const int n_pass = (rep + RC - 1) / RC;            // workgroups per K/V head: RC query heads each
+    const int work = xcd_remap(blockIdx.x, gridDim.x);
+    const int r0 = (work % n_pass) * RC, h = (work / n_pass) % n_kv_heads, b = work / (n_pass * n_kv_heads);
+    const int tid = threadIdx.x, wave = tid >> 6;
     const int piece = tid % PPT, tl = tid / PPT;
     const int wave_t0 = (tid & ~63) / PPT;  // first token of this wave within a pass
     const int n32 = dkv >> 3, ng = dkv >> 6;
@@ -83,9 +94,8 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
     const float scale = 1.0f / sqrtf((float)DH);
     const size_t row0 = (size_t)b * capacity;
 
-    for (int r0 = 0; r0 < rep; r0 += RC) {
+    {
         const int nr = min(RC, rep - r0);
-        __syncthreads();                    // qp, sc, red of the previous pass are done with
         if (tid < RC * (DH / 2)) {
             const int r = tid / (DH / 2), i = tid % (DH / 2);
             const int hq = min(h * rep + r0 + r, h * rep + rep - 1);
@@ -169,12 +179,14 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
             float alpha[RC], m_new[RC], sum[RC];
 #pragma unroll
             for (int r = 0; r < RC; ++r) {
-                const float tm = fmaxf(fmaxf(wred[0][r][0], wred[0][r][1]), fmaxf(wred[0][r][2], wred[0][r][3]));
+                float tm = wred[0][r][0];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) tm = fmaxf(tm, wred[0][r][w]);
                 m_new[r] = fmaxf(m_run[r], tm);
                 alpha[r] = __expf(m_run[r] - m_new[r]);      // 0 on the first tile
                 m_run[r] = m_new[r];
                 sum[r] = 0.0f;
-                for (int t = tid; t < tn; t += 256) {
+                for (int t = tid; t < tn; t += DEC_THREADS) {
                     const float p = __expf(sc[r][t] - m_new[r]);
                     sc[r][t] = p;
                     sum[r] += p;
@@ -185,7 +197,10 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
             __syncthreads();                // probabilities and wave sums visible
 #pragma unroll
             for (int r = 0; r < RC; ++r) {
-                l_run[r] = l_run[r] * alpha[r] + (((wred[1][r][0] + wred[1][r][1]) + wred[1][r][2]) + wred[1][r][3]);
+                float ts = wred[1][r][0];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) ts += wred[1][r][w];
+                l_run[r] = l_run[r] * alpha[r] + ts;
 #pragma unroll
                 for (int e = 0; e < 32; ++e) acc[r][e] *= alpha[r];
             }
@@ -215,24 +230,24 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(
             }
             __syncthreads();                // the tile's scores have been consumed
         }
-        // ---- the token lanes meet in LDS, half of them at a time, summed in lane order (red is
+        // ---- the token lanes meet in LDS, 128 of them at a time, summed in lane order (red is
         // laid out [channel][token lane] so that the lanes of a wave write consecutive words; the
         // loop over r is unrolled to keep acc in registers)
 #pragma unroll
         for (int r = 0; r < RC; ++r) {
             if (r >= nr) break;
             float out = 0.0f;
-            for (int half = 0; half < 2; ++half) {
+            for (int round = 0; round < NQ; ++round) {
                 __syncthreads();
-                if (tl / (TP / 2) == half) {
+                if (tl / (TP / NQ) == round) {
 #pragma unroll
-                    for (int e = 0; e < 32; ++e) red[e * (128 + 1) + (tl % (TP / 2)) * PPT + piece] = acc[r][e];
+                    for (int e = 0; e < 32; ++e) red[e * (128 + 1) + (tl % (TP / NQ)) * PPT + piece] = acc[r][e];
                 }
                 __syncthreads();
                 if (tid < DH) {
                     const int pc = tid >> 5, e = tid & 31;
 #pragma unroll 4
-                    for (int i = 0; i < TP / 2; ++i) out += red[e * (128 + 1) + i * PPT + pc];
+                    for (int i = 0; i < TP / NQ; ++i) out += red[e * (128 + 1) + i * PPT + pc];
                 }
             }
             if (tid < DH) o[(size_t)b * d + (h * rep + r0 + r) * DH + tid] = (f16)(out / l_run[r]);
@@ -288,13 +303,14 @@ extern "C" int quota_attention_decode_gqa(const void *q_f16, int Hq, const quota
     hipStream_t st = (hipStream_t)stream;
     const double rows = (double)cache->B * longest;
     ProfScope prof(QUOTA_K_ATTENTION_DECODE, 4.0 * rows * d, rows * (dkv + dkv / 16.0) + 4.0 * cache->B * d, st);
-    dim3 grid(cache->H, cache->B), block(256);
+    const int rc = rep == 1 ? 1 : 2;
+    dim3 grid(cache->H * cache->B * ((rep + rc - 1) / rc)), block(DEC_THREADS);
     auto kernel = cache->dh == 128 ? (rep == 1 ? decode_attention_kernel<128, 1> : decode_attention_kernel<128, 2>)
                                    : (rep == 1 ? decode_attention_kernel<64, 1> : decode_attention_kernel<64, 2>);
     kernel<<<grid, block, 0, st>>>(
         (const f16 *)q_f16, d, dkv, rep, (const uint32_t *)cache->k_codes, (const f16 *)cache->k_scales,
         (const uint32_t *)cache->v_codes, (const f16 *)cache->v_scales, cache->capacity, cache->len,
-        cache->step_dev, cache->max_steps, (f16 *)o_f16);
+        cache->step_dev, cache->max_steps, (f16 *)o_f16, cache->H);
     QUOTA_RETURN_IF_LAUNCH_FAILED();
     return QUOTA_OK;
 }
