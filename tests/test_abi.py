@@ -167,3 +167,36 @@ def test_gemm_variant_setter(lib):
     assert lib.quota_set_gemm_variant(5) == -2 and lib.quota_set_gemm_variant(-2) == -2
     for v in (0, 4, -1):
         assert lib.quota_set_gemm_variant(v) == 0
+
+
+def test_profiler_calls_validate_before_any_device_work(lib):
+    """The calibration-time entry points (Eq. 1) reject bad descriptors on the host: no GPU is needed
+    to see the error codes, and the workspace queries answer 0 for a layer they would reject."""
+    from paper_2604_17320_amd import binding as qb
+    lib.quota_fp_block_workspace_bytes.restype = C.c_size_t
+    lib.quota_profile_block_workspace_bytes.restype = C.c_size_t
+    fake = 0x1000                                      # never dereferenced: every check below fails first
+    good = qb.FpLayer(8, 64, 1376, 0, 1e-5, fake, fake, fake, fake, fake, fake, fake, fake, 64)
+    assert lib.quota_fp_block_workspace_bytes(C.byref(good), 2, 80) > 0
+    ws = C.c_void_p(fake)
+    x = C.c_void_p(fake)
+    assert lib.quota_fp_block(None, x, x, 2, 80, x, ws, None) == qb.ERR_NULL
+    assert lib.quota_fp_block(C.byref(good), None, x, 2, 80, x, ws, None) == qb.ERR_NULL
+    assert lib.quota_fp_block(C.byref(good), x, x, 0, 80, x, ws, None) == qb.ERR_INVALID_ARG
+    for bad in (qb.FpLayer(8, 96, 1376, 0, 1e-5, fake, fake, fake, fake, fake, fake, fake, fake, 64),     # head size
+                qb.FpLayer(8, 64, 1376, 3, 1e-5, fake, fake, fake, fake, fake, fake, fake, fake, 64),     # H % Hkv
+                qb.FpLayer(8, 64, 1380, 0, 1e-5, fake, fake, fake, fake, fake, fake, fake, fake, 64)):    # F % 32
+        assert lib.quota_fp_block(C.byref(bad), x, x, 2, 80, x, ws, None) == qb.ERR_SHAPE
+        assert lib.quota_fp_block_workspace_bytes(C.byref(bad), 2, 80) == 0
+    no_w = qb.FpLayer(8, 64, 1376, 0, 1e-5, fake, fake, None, fake, fake, fake, fake, fake, 64)
+    assert lib.quota_fp_block(C.byref(no_w), x, x, 2, 80, x, ws, None) == qb.ERR_NULL
+    assert lib.quota_activation_deviation(None, x, 2, C.c_long(10), x, x, None) == qb.ERR_NULL
+    assert lib.quota_activation_deviation(x, x, 0, C.c_long(10), x, x, None) == qb.ERR_INVALID_ARG
+    assert lib.quota_activation_deviation(x, x, 2, C.c_long(-1), x, x, None) == qb.ERR_INVALID_ARG
+    # the two layers of a profile must describe the same block
+    w = qb.Weights(64, 64, fake, fake)
+    lq = qb.Layer(4, 64, 1376, 1e-5, fake, fake, w, w, w, w, fake, fake, 64, 0)
+    cache = qb.KVCache(2, 100, 4, 64, 0, fake, fake, fake, fake)
+    assert lib.quota_profile_block(C.byref(lq), C.byref(good), x, x, 2, 80, C.byref(cache), x, x, ws, None) == qb.ERR_SHAPE
+    assert lib.quota_profile_block(C.byref(lq), C.byref(good), x, x, 2, 80, None, x, x, ws, None) == qb.ERR_NULL
+    assert cache.len == 0
