@@ -117,7 +117,12 @@ def bandwidth_kernels(shape, seed, reps=12, with_gemm=False):
         qb.quota_attention_decode(q1, dcaches[i % 12].desc, o1)
 
     Md = float(M) * d
+    csrc = [torch.ones(64 << 20, dtype=torch.float32, device="cuda") for _ in range(2)]     # 2 x 256 MiB
+    cdst = torch.empty_like(csrc[0])
     cases = [
+        # the measuring stick: a plain elementwise copy (torch's kernel, not the library's) of 256 MiB in +
+        # 256 MiB out; what it reaches is the practical ceiling the rates below are also set against
+        ("copy (plain elementwise, reference)", lambda i: torch.mul(csrc[i % 2], 1.0, out=cdst), 2.0 * (256 << 20)),
         ("quantize_act", lambda i: qb.quota_quantize_act(xs[i % 4], M, d, d, qa, sa), 2.5 * Md),
         ("quantize_act (+ m_mag, m_res)", lambda i: qb.quota_quantize_act(xs[i % 4], M, d, d, qa, sa, sq, rq), 2.5 * Md),
         ("rmsnorm_quantize_act", lambda i: qb.quota_rmsnorm_quantize_act(xs[i % 4], M, d, d, gamma, 1e-5, qa, sa), 2.5 * Md),
@@ -142,6 +147,10 @@ def bandwidth_kernels(shape, seed, reps=12, with_gemm=False):
         us = e0.elapsed_time(e1) * 1e3 / reps
         out[name] = dict(avg_us=round(us, 2), MB=round(nbytes / 1e6, 1), GBps=round(nbytes / us / 1e3, 1),
                          frac_hbm_peak=round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4))
+    copy_rate = out["copy (plain elementwise, reference)"]["GBps"]
+    for rec in out.values():
+        rec["frac_copy_rate"] = round(rec["GBps"] / copy_rate, 4)
+    del csrc, cdst
     if with_gemm:
         w = torch.randn((3 * d, d), generator=g, device="cuda", dtype=torch.float32) * 0.02
         lin = PackedLinear.from_fp32(w)
@@ -162,7 +171,8 @@ def bandwidth_kernels(shape, seed, reps=12, with_gemm=False):
                                     frac_int8_peak=round(ops / us / 1e6 / PEAK_INT8_TOPS, 4))
     return dict(shape=f"batch {B} x {N} tokens, d={d}, F={F} ({M} rows)", reps=reps,
                 note="algorithmic bytes (inputs once + outputs once, int4 as half bytes) / event time; inputs rotate over "
-                     "buffers larger than the last-level cache", kernels=out)
+                     "buffers larger than the last-level cache; frac_copy_rate = against the plain copy measured in the same run",
+                kernels=out)
 
 
 def serving_decode(shape, stack, budgets, seed, steps=32):

@@ -135,14 +135,20 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
     Pack16 v[NCH];
     float a_raw = 0.0f;
     double ss = 0.0;
-    float4 ga[NCH][2];
+    // wave-per-row launches are long (thousands of rows): the gains are fetched where they are used
+    // (they stay in cache) so that more waves fit on a SIMD; workgroup-per-row launches are short and
+    // latency counts, so there every load is issued up front
+    constexpr bool GAINS_EARLY = GROUP != 64;
+    float4 ga[GAINS_EARLY ? NCH : 1][2];
 #pragma unroll
     for (int r = 0; r < NCH; ++r) {
         const int c = min(lane + GROUP * r, nchunk - 1);
         v[r].u = xr[c];
-        const float4 *gp = reinterpret_cast<const float4 *>(gamma + 8 * c);
-        ga[r][0] = gp[0];
-        ga[r][1] = gp[1];
+        if (GAINS_EARLY) {
+            const float4 *gp = reinterpret_cast<const float4 *>(gamma + 8 * c);
+            ga[r][0] = gp[0];
+            ga[r][1] = gp[1];
+        }
     }
 #pragma unroll
     for (int r = 0; r < NCH; ++r) {
@@ -158,6 +164,13 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
     }
     double zero = 0.0;
     group_reduce<GROUP>(a_raw, ss, zero, sm);
+    if (!GAINS_EARLY) {
+        // the row stays packed (32 registers for 4096 columns): without this the compiler keeps the 64
+        // converted floats of the first pass alive for the second one
+#pragma unroll
+        for (int r = 0; r < NCH; ++r)
+            asm volatile("" : "+v"(v[r].u.x), "+v"(v[r].u.y), "+v"(v[r].u.z), "+v"(v[r].u.w));
+    }
     float rn = (float)(1.0 / sqrt(ss / (double)d + (double)eps));
     float s_raw = 1.0f, inv_raw = 0.0f;
     if (a_raw != 0.0f) { s_raw = a_raw / 7.0f; inv_raw = 7.0f / a_raw; }
@@ -167,7 +180,9 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
     for (int r = 0; r < NCH; ++r) {
         int c = lane + GROUP * r;
         if (c < nchunk) {
-            const float4 g0 = ga[r][0], g1 = ga[r][1];
+            const float4 *gp = reinterpret_cast<const float4 *>(gamma + 8 * c);
+            const float4 g0 = GAINS_EARLY ? ga[GAINS_EARLY ? r : 0][0] : gp[0];
+            const float4 g1 = GAINS_EARLY ? ga[GAINS_EARLY ? r : 0][1] : gp[1];
             float gm[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -185,6 +200,8 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_quantize_act_kernel(
             }
             if (h_out) reinterpret_cast<uint4 *>(h_out + (size_t)row * d)[c] = v[r].u;
         }
+        // keep the compiler from hoisting every chunk's gain loads to the top (that costs 64 registers)
+        if (!GAINS_EARLY) __builtin_amdgcn_sched_barrier(0);
     }
     group_reduce<GROUP>(a, rs, zero, sm);
     float s;
