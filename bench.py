@@ -169,6 +169,31 @@ def bandwidth_kernels(shape, seed, reps=12, with_gemm=False):
         us, ops = e0.elapsed_time(e1) * 1e3 / reps, 2.0 * M * 3 * d * d
         out["w4a4_gemm qkv"] = dict(avg_us=round(us, 2), TOPs=round(ops / us / 1e6, 1),
                                     frac_int8_peak=round(ops / us / 1e6 / PEAK_INT8_TOPS, 4))
+        del lin, y
+        # prefill attention where it is a sizeable share of a layer: the high-resolution 13B shape
+        # (batch 4, 2880 + 64 tokens, 40 heads of 128), forward pass and cue pass
+        Ba, Na, Ha, Nva = 4, 2944, 40, 2880
+        qa_, ka_, va_ = (rnd(Ba * Na, Ha * dh) for _ in range(3))
+        oa_ = torch.empty_like(qa_)
+        cmi, cmv = (torch.empty((Ba, Nva), dtype=torch.float32, device="cuda") for _ in range(2))
+        wsa = torch.empty(qb.quota_attention_workspace_bytes(Ba, Na, Ha, dh), dtype=torch.uint8, device="cuda")
+        for name, cues in (("attention_prefill forward (batch 4 x 2944 tokens, 40 heads)", False),
+                           ("attention_prefill forward + cue pass", True)):
+            fn = lambda: qb.quota_attention_prefill(qa_, ka_, va_, Ba, Na, Ha, dh, 0, Nva, oa_,
+                                                    cmi if cues else None, cmv if cues else None, wsa)
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / reps
+            pairs = Na * (Na + 1) / 2.0
+            flops = 4.0 * Ba * Ha * dh * pairs + (2.0 * Ba * Ha * dh * (pairs - (Na - Nva) * (Na - Nva + 1) / 2.0) if cues else 0.0)
+            out[name] = dict(avg_us=round(us, 2), TFLOPs=round(flops / us / 1e6, 1),
+                             frac_fp16_peak=round(flops / us / 1e6 / 2500.0, 4))
     return dict(shape=f"batch {B} x {N} tokens, d={d}, F={F} ({M} rows)", reps=reps,
                 note="algorithmic bytes (inputs once + outputs once, int4 as half bytes) / event time; inputs rotate over "
                      "buffers larger than the last-level cache; frac_copy_rate = against the plain copy measured in the same run",
