@@ -57,6 +57,30 @@ def test_attention_decode_gqa(qb):
     assert e.value.code == qb.ERR_SHAPE
 
 
+@pytest.mark.parametrize("B,L,Hq,Hkv,dh", [
+    (2, 700, 28, 4, 128),      # 7 query heads per K/V head: the last workgroup of a head serves one query head
+    (3, 513, 6, 3, 64),        # head_dim 64, one row past a 512-row tile, a grid that is no multiple of 8
+    (1, 512, 4, 1, 128),       # exactly one tile, one K/V head
+    (5, 1100, 10, 5, 128),     # three tiles of the running softmax
+])
+def test_attention_decode_gqa_shapes(qb, B, L, Hq, Hkv, dh):
+    """Grouped heads through the decode attention's workgroup layout: one workgroup per (sequence,
+    K/V head, pair of query heads), dealt to the XCDs in contiguous ranges."""
+    from paper_2604_17320_amd.model import KVCache4
+    r = wl.rng(95, "gqa-dec", B, L, Hq)
+    kc, ks, _ = oracle.kv_quant((r.standard_normal((B * L, Hkv * dh)) * 1.5).astype(np.float16))
+    vc, vs, _ = oracle.kv_quant(r.standard_normal((B * L, Hkv * dh)).astype(np.float16))
+    sh = lambda a: a.reshape(B, L, -1)
+    c = dict(kc=sh(kc), ks=sh(ks), vc=sh(vc), vs=sh(vs))
+    q = r.standard_normal((B, Hq * dh)).astype(np.float16)
+    ref = oracle.decode_attention(q, c["kc"], c["ks"], c["vc"], c["vs"], Hq, dh, Hkv)
+    cache = KVCache4(B, L + 3, Hkv, dh)
+    fill_cache(cache, c, L)
+    o = torch.full((B, Hq * dh), float("nan"), dtype=torch.float16, device="cuda")     # every output must be written
+    qb.quota_attention_decode_gqa(dev(q), Hq, cache.desc, o)
+    assert close_f16(host(o), ref)
+
+
 def build_gqa_layer(d, H, Hkv, dh, F, seed, n_pos):
     from paper_2604_17320_amd.model import PackedLinear, PrefillLayer
     r = wl.rng(seed, "gqa-layer")

@@ -24,14 +24,18 @@ def qb():
     return binding
 
 
-def small_stack(n_layers, B, budgets, decode_capacity=0):
+def small_stack(n_layers, B, budgets, decode_capacity=0, Hkv=None):
     from paper_2604_17320_amd.model import PrefillStack
     base = wl.CONFIGS[0]
     shape = wl.Shape("stack", d=base.d, H=base.H, F=base.F, layers=n_layers, B=B, Nv=base.Nv, Nt=base.Nt,
                      n_outlier=base.n_outlier, vis_begin=0)
     Ws, Ls = [], []
     for l in range(n_layers):
-        W, L, cos, sin = build_layer(shape, 10 + l, gamma_random=True)
+        if Hkv is None:
+            W, L, cos, sin = build_layer(shape, 10 + l, gamma_random=True)
+        else:                                   # grouped K/V heads
+            from test_gpu_gqa import build_gqa_layer
+            W, L, cos, sin = build_gqa_layer(shape.d, shape.H, Hkv, shape.dh, shape.F, 10 + l, shape.N + 8)
         Ws.append(W)
         Ls.append(L)
     stack = PrefillStack(Ls, B, shape.N, 0, shape.Nv, budgets, decode_capacity=decode_capacity)
@@ -165,13 +169,15 @@ def test_stack_prunes_at_candidate_layers_only(qb):
             assert np.array_equal(got_sc, o["score"])
 
 
-def test_stack_decode_loop_in_a_hip_graph(qb):
+@pytest.mark.parametrize("Hkv", [None, 2])
+def test_stack_decode_loop_in_a_hip_graph(qb, Hkv):
     """A decode loop captured once and replayed: the cache length lives on the device (step count read
     by the kernels), the new token's input and position are refreshed in place between replays.
-    Every replay must give the bits of the eager step with host-side lengths, appended rows included."""
+    Every replay must give the bits of the eager step with host-side lengths, appended rows included.
+    Once with a K/V head per query head, once with grouped K/V heads (8 query heads on 2)."""
     budgets = [64, 30, 12]
     B, steps = 2, 4
-    shape, Ws, stack, cos, sin = small_stack(3, B, budgets, decode_capacity=steps + 1)
+    shape, Ws, stack, cos, sin = small_stack(3, B, budgets, decode_capacity=steps + 1, Hkv=Hkv)
     x, pos = dev(wl.hidden_state(shape, 6)), dev(wl.positions(shape))
     stack.run(x, pos)
     torch.cuda.synchronize()
