@@ -249,7 +249,7 @@ void quota_score_params_default(quota_score_params *p);
  * and rescales to [0,1] (0.5 for a flat metric); then
  * score = ((w_m*g_mag + w_c*g_inter) + w_s*g_intra) + w_r*g_res in fp32.
  * normed_opt receives the normalised metrics [4][B][Nv] (mag, inter, intra,
- * res).  Requires 0 <= pct_lo <= pct_hi <= 100, Nv <= 3072. */
+ * res).  Requires 0 <= pct_lo <= pct_hi <= 100, Nv <= 8192. */
 int quota_score_tokens(const float *sumsq, const float *ressq,
                        const float *cm_inter, const float *cm_intra, int B,
                        int Nv, const quota_score_params *p, float *score,
@@ -269,7 +269,7 @@ int quota_score_tokens_from_hidden(const void *v_f16, int B, int Nv, int d,
  * ties broken towards the lower index, emitted in ascending index order.
  * score fp32 [B][Nv]; keep_idx int32 [B][min(K,Nv)].  K is the integer budget
  * K_l = ceil(r_l * V0) (Eq. 5) -- the rounding is the recipe's job.  NaN
- * scores rank lowest.  Requires Nv <= 3072, K >= 0. */
+ * scores rank lowest.  Requires Nv <= 8192, K >= 0. */
 int quota_topk_prune(const float *score, int B, int Nv, int K,
                      int32_t *keep_idx, void *stream);
 
@@ -345,7 +345,7 @@ size_t quota_prefill_workspace_bytes(const quota_layer *L, int B, int N);
  * descriptors (cache->len, st->N, st->Nv) move only after the last one, so a
  * call that returns an error has enqueued nothing and changed nothing:
  * QUOTA_ERR_SHAPE for dh not 64 / 128, H % Hkv != 0, F % 32 != 0, d > 16384,
- * F > 32768, more than 3072 visual tokens in a candidate layer, weight shapes
+ * F > 32768, more than 8192 visual tokens in a candidate layer, weight shapes
  * that do not fit the layer or the packer; QUOTA_ERR_CAPACITY when the cache
  * cannot take n_keep more rows. */
 int quota_prefill_layer(const quota_layer *L, quota_state *st, int K_l,

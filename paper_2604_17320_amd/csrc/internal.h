@@ -73,7 +73,7 @@ int quota_internal_advance_step(int32_t *step_dev, hipStream_t st);
 
 // Limits that the kernels behind the layer calls enforce, for the up-front checks of the layer
 // calls (a call that returns an error must not have enqueued anything).
-#define QUOTA_MAX_SCORED_TOKENS 3072      // visual tokens per sequence the score / top-k kernel holds in LDS
+#define QUOTA_MAX_SCORED_TOKENS 8192      // visual tokens per sequence the score / top-k kernel holds in LDS
 #define QUOTA_MAX_DECODE_ROWS 8192        // cached rows per sequence the decode attention softmaxes over
 #define QUOTA_MAX_MODEL_WIDTH 16384       // d: the compaction gather keeps a row in registers
 #define QUOTA_MAX_ROW_COLS 32768          // widest row of the row quantizers (the FFN width F)

@@ -100,9 +100,10 @@ constexpr int SCORE_THREADS = 1024;
 // eight percentile bounds (one wave per bound, keys in LDS), then fuses the score of every
 // token.  1024 threads: the load phase is one memory round trip deep -- a thread owns a
 // quarter of the heads of up to three tokens and issues all those loads back to back.
-// mk: 4*MAXV keys, hist: 8*256 ints, lohi: 8 floats.
+// mk: 4*cap keys (cap >= Nv: the stride between the four metrics), hist: 8*256 ints, lohi: 8 floats.
+template <int PER>      // tokens per thread of the fusion pass: Nv <= PER * SCORE_THREADS
 __device__ void score_phase(const MetricSrc &src, int B, int Nv, int b, const quota_score_params &p,
-                            float *__restrict__ score, float *__restrict__ normed, uint32_t *mk,
+                            float *__restrict__ score, float *__restrict__ normed, uint32_t *mk, int cap,
                             int *hist, float *lohi)
 {
     const int tid = threadIdx.x, wave = tid >> 6;
@@ -138,39 +139,38 @@ __device__ void score_phase(const MetricSrc &src, int B, int Nv, int b, const qu
                     const float m_inter = a * invH, m_intra = c * invH;
                     if (src.cm_out_inter) src.cm_out_inter[src.ocm + i] = m_inter;
                     if (src.cm_out_intra) src.cm_out_intra[src.ocm + i] = m_intra;
-                    mk[1 * MAXV + i] = float_key(m_inter);
-                    mk[2 * MAXV + i] = float_key(m_intra);
+                    mk[1 * cap + i] = float_key(m_inter);
+                    mk[2 * cap + i] = float_key(m_intra);
                 }
             }
         }
     }
     for (int i = tid; i < Nv; i += SCORE_THREADS) {
         if (!src.partial) {
-            mk[1 * MAXV + i] = float_key(src.cm_inter[src.ocm + i]);
-            mk[2 * MAXV + i] = float_key(src.cm_intra[src.ocm + i]);
+            mk[1 * cap + i] = float_key(src.cm_inter[src.ocm + i]);
+            mk[2 * cap + i] = float_key(src.cm_intra[src.ocm + i]);
         }
-        mk[0 * MAXV + i] = float_key(sqrtf(src.sumsq[src.osq + i]));    // m_mag
-        mk[3 * MAXV + i] = float_key(sqrtf(src.ressq[src.osq + i]));    // m_res
+        mk[0 * cap + i] = float_key(sqrtf(src.sumsq[src.osq + i]));    // m_mag
+        mk[3 * cap + i] = float_key(sqrtf(src.ressq[src.osq + i]));    // m_res
     }
     __syncthreads();
     const int r_lo = (p.pct_lo * (Nv - 1) + 50) / 100, r_hi = (p.pct_hi * (Nv - 1) + 50) / 100;
     if (wave < 8) {                                 // wave 2m: low bound of metric m, wave 2m+1: high bound
-        const uint32_t *keys = mk + (wave >> 1) * MAXV;
+        const uint32_t *keys = mk + (wave >> 1) * cap;
         auto key_at = [&](int i) { return keys[i]; };
         uint32_t kb = wave_radix_select(key_at, Nv, (wave & 1) ? r_hi : r_lo, hist + 256 * wave);
         if ((tid & 63) == 0) lohi[wave] = key_float(kb);
     }
     __syncthreads();
-    constexpr int PER = MAXV / SCORE_THREADS;
     float sc[PER];
 #pragma unroll
     for (int r = 0; r < PER; ++r) {
         const int i = tid + SCORE_THREADS * r;
         if (i < Nv) {
-            float g0 = robust_unit(key_float(mk[0 * MAXV + i]), lohi[0], lohi[1]);
-            float g1 = robust_unit(key_float(mk[1 * MAXV + i]), lohi[2], lohi[3]);
-            float g2 = robust_unit(key_float(mk[2 * MAXV + i]), lohi[4], lohi[5]);
-            float g3 = robust_unit(key_float(mk[3 * MAXV + i]), lohi[6], lohi[7]);
+            float g0 = robust_unit(key_float(mk[0 * cap + i]), lohi[0], lohi[1]);
+            float g1 = robust_unit(key_float(mk[1 * cap + i]), lohi[2], lohi[3]);
+            float g2 = robust_unit(key_float(mk[2 * cap + i]), lohi[4], lohi[5]);
+            float g3 = robust_unit(key_float(mk[3 * cap + i]), lohi[6], lohi[7]);
             float a = p.w_m * g0;
             float c = p.w_c * g1;
             float s = p.w_s * g2;
@@ -243,19 +243,22 @@ __device__ void topk_phase(const uint32_t *keys, int Nv, int K, int32_t *__restr
 
 // K < 0: score only.  When K >= 0 the indices of the min(K, Nv) best tokens of
 // sequence b go to keep_idx[b][0..min(K,Nv)).
+template <int PER>
 __global__ __launch_bounds__(SCORE_THREADS) void score_topk_kernel(MetricSrc src, long stride_sq, int B, int Nv,
                                                          quota_score_params p,
                                                          float *__restrict__ score,
                                                          float *__restrict__ normed, int K,
-                                                         int32_t *__restrict__ keep_idx)
+                                                         int32_t *__restrict__ keep_idx, int cap)
 {
-    __shared__ uint32_t mk[4 * MAXV];
-    __shared__ int hist[8 * 256];
-    __shared__ float lohi[8];
+    // LDS sized by the launch for this Nv: 4 * cap keys, 8 histograms of 256 bins, 8 bounds
+    extern __shared__ __align__(16) uint32_t score_lds[];
+    uint32_t *mk = score_lds;
+    int *hist = reinterpret_cast<int *>(mk + 4 * cap);
+    float *lohi = reinterpret_cast<float *>(hist + 8 * 256);
     const int b = blockIdx.x;
     src.osq = (size_t)b * stride_sq;
     src.ocm = (size_t)b * Nv;
-    score_phase(src, B, Nv, b, p, score, normed, mk, hist, lohi);
+    score_phase<PER>(src, B, Nv, b, p, score, normed, mk, cap, hist, lohi);
     if (K < 0) return;
     const int k = K < Nv ? K : Nv;
     int32_t *out = keep_idx + (size_t)b * k;
@@ -286,6 +289,32 @@ __global__ __launch_bounds__(256) void topk_kernel(const float *__restrict__ sco
     if (threadIdx.x < 64) topk_phase(keys, Nv, K, out, hist);
 }
 
+// Launches the score (+ top-k) kernel with the LDS its Nv needs: up to 136 KB at 8192 tokens, which
+// is above the default limit of a launch and has to be granted once per device.
+int launch_score_topk(const MetricSrc &src, long stride_sq, int B, int Nv, const quota_score_params &p,
+                      float *score, float *normed, int K, int32_t *keep_idx, hipStream_t st)
+{
+    const int cap = (Nv + 63) & ~63;
+    const size_t lds = ((size_t)4 * cap + 8 * 256 + 8) * sizeof(uint32_t);
+    if (Nv > 3 * SCORE_THREADS) {          // the widest instantiation: up to 136 KB, above a launch's default 64 KB
+        static bool granted[64];
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return QUOTA_ERR_HIP;
+        if (!granted[dev]) {
+            const size_t most = ((size_t)4 * MAXV + 8 * 256 + 8) * sizeof(uint32_t);
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(score_topk_kernel<MAXV / SCORE_THREADS>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)most) != hipSuccess)
+                return QUOTA_ERR_HIP;
+            granted[dev] = true;
+        }
+    }
+    auto kernel = Nv <= SCORE_THREADS ? score_topk_kernel<1>
+                  : Nv <= 3 * SCORE_THREADS ? score_topk_kernel<3> : score_topk_kernel<MAXV / SCORE_THREADS>;
+    kernel<<<dim3(B), dim3(SCORE_THREADS), lds, st>>>(src, stride_sq, B, Nv, p, score, normed, K, keep_idx, cap);
+    QUOTA_RETURN_IF_LAUNCH_FAILED();
+    return QUOTA_OK;
+}
+
 int check_score_args(const float *sumsq, const float *ressq, const float *cm_inter,
                      const float *cm_intra, int B, int Nv, const quota_score_params *p, float *score)
 {
@@ -307,10 +336,7 @@ int quota_internal_score(const float *sumsq, const float *ressq, long stride_sq,
     if (Nv == 0) return QUOTA_OK;
     ProfScope prof(QUOTA_K_SCORE_TOKENS, 0, 20.0 * B * Nv, st);
     MetricSrc src{sumsq, ressq, cm_inter, cm_intra, nullptr, 0, nullptr, nullptr, 0, 0};
-    score_topk_kernel<<<dim3(B), dim3(SCORE_THREADS), 0, st>>>(src, stride_sq, B, Nv, *p, score, normed, -1,
-                                                     nullptr);
-    QUOTA_RETURN_IF_LAUNCH_FAILED();
-    return QUOTA_OK;
+    return launch_score_topk(src, stride_sq, B, Nv, *p, score, normed, -1, nullptr, st);
 }
 
 // score + top-k in one launch (the layer's path).  The attention cues come either as
@@ -333,10 +359,7 @@ int quota_internal_score_topk(const float *sumsq, const float *ressq, long strid
     ProfScope prof(QUOTA_K_SCORE_TOKENS, 0,
                    (partial ? 8.0 * H + 8 : 20.0) * B * Nv + 4.0 * B * (K < Nv ? K : Nv), st);
     MetricSrc src{sumsq, ressq, cm_inter, cm_intra, partial, H, cm_out_inter, cm_out_intra, 0, 0};
-    score_topk_kernel<<<dim3(B), dim3(SCORE_THREADS), 0, st>>>(src, stride_sq, B, Nv, *p, score, nullptr, K,
-                                                     keep_idx);
-    QUOTA_RETURN_IF_LAUNCH_FAILED();
-    return QUOTA_OK;
+    return launch_score_topk(src, stride_sq, B, Nv, *p, score, nullptr, K, keep_idx, st);
 }
 
 extern "C" void quota_score_params_default(quota_score_params *p)

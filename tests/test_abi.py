@@ -135,7 +135,7 @@ def test_layer_calls_reject_every_downstream_limit_before_touching_anything(lib)
     assert prefill(_fake_layer(binding, H=160), 1, 640, 576, 173) == ERR_SHAPE            # d = 20480 > 16384
     assert prefill(_fake_layer(binding, dh=96), 1, 640, 576, 173) == ERR_SHAPE
     assert prefill(_fake_layer(binding, Hkv=5), 1, 640, 576, 173) == ERR_SHAPE            # 32 % 5
-    assert prefill(ok, 1, 3200, 3100, 500) == ERR_SHAPE                                   # 3100 scored tokens
+    assert prefill(ok, 1, 8400, 8300, 500) == ERR_SHAPE                                   # 8300 scored tokens
     assert prefill(ok, 1, 640, 576, 173, cache_len=10, capacity=200) == ERR_CAPACITY      # 10 + 237 > 200
     assert prefill(ok, 1, 640, 576, 173, cache_len=-1) == ERR_INVALID
     assert prefill(ok, 1, 640, 576, -2) == ERR_INVALID
@@ -148,7 +148,7 @@ def test_layer_calls_reject_every_downstream_limit_before_touching_anything(lib)
     assert prefill(bad_w, 1, 640, 576, 173) == ERR_SHAPE
     # a layer outside the candidate set may carry any number of visual tokens (nothing is scored) -- the
     # only thing left to reject here is the capacity
-    assert prefill(ok, 1, 3200, 3100, -1, capacity=100) == ERR_CAPACITY
+    assert prefill(ok, 1, 8400, 8300, -1, capacity=100) == ERR_CAPACITY
 
     def decode(L, B, cache_len, capacity):
         cache = binding.KVCache(B, capacity, L.Hkv or L.H, L.dh, cache_len, 0x1000, 0x1000, 0x1000, 0x1000)

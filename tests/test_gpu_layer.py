@@ -112,6 +112,7 @@ CASES = [
     ("keep_none", dict(), 0),
     ("batch2_prefix", dict(B=2, vis_begin=3, Nt=9), 19),
     ("no_visual", dict(Nv=0, Nt=40), 5),
+    ("long_visual_prefix", dict(Nv=4100, Nt=28), 1000),   # more scored tokens than fit the default LDS limit of a launch
 ]
 
 

@@ -307,7 +307,7 @@ def _metrics(B, Nv, seed):
             r.uniform(0, 0.2, (B, Nv)).astype(np.float32), r.uniform(0, 3, (B, Nv)).astype(np.float32))
 
 
-@pytest.mark.parametrize("B,Nv", [(1, 64), (3, 576), (2, 2880), (1, 1), (1, 3072), (2, 7)])
+@pytest.mark.parametrize("B,Nv", [(1, 64), (3, 576), (2, 2880), (1, 1), (1, 3072), (2, 7), (2, 4100), (1, 8192)])
 def test_score_tokens_bit_exact(qb, B, Nv):
     ss, rs, ci, cv = _metrics(B, Nv, 61)
     if Nv > 4:
@@ -340,7 +340,7 @@ def test_score_tokens_from_hidden(qb):
     assert np.array_equal(host(sc), sc_ref)
 
 
-@pytest.mark.parametrize("B,Nv", [(1, 64), (3, 576), (2, 2880), (1, 3072), (2, 5)])
+@pytest.mark.parametrize("B,Nv", [(1, 64), (3, 576), (2, 2880), (1, 3072), (2, 5), (2, 4100), (1, 8192)])
 def test_topk_prune_bit_exact(qb, B, Nv):
     r = wl.rng(71, "topk", B, Nv)
     sc = (np.round(r.uniform(0, 1, (B, Nv)) * 50) / 50).astype(np.float32)     # plenty of ties
@@ -361,4 +361,4 @@ def test_topk_prune_bit_exact(qb, B, Nv):
     qb.quota_topk_prune(allsame, B, Nv, k, out)
     assert np.array_equal(host(out), np.tile(np.arange(k, dtype=np.int32), (B, 1)))
     with pytest.raises(qb.QuotaError):
-        qb.quota_topk_prune(scd, B, 5000, 3, out)
+        qb.quota_topk_prune(scd, B, 8200, 3, out)
