@@ -108,6 +108,8 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
                 s[sb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[t], s[sb], 0, 0, 0);
             }
         }
+        // the maximum is taken on the raw logits (the scale is positive) and the scale is folded into
+        // the exponent's fused multiply-add: exp2(s * scale - m), one instruction per score less
         float mx = -INFINITY;
         // only a tile that reaches this wave's diagonal or the end of the sequence needs the mask
         if (kt0 + KT - 1 > qw0 || kt0 + KT > N) {
@@ -116,8 +118,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     int key = kt0 + 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
-                    float v = s[sb][r] * scale_log2;
-                    v = (key <= qi && key < N) ? v : -INFINITY;
+                    float v = (key <= qi && key < N) ? s[sb][r] : -INFINITY;
                     s[sb][r] = v;
                     mx = fmaxf(mx, v);
                 }
@@ -125,14 +126,10 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
 #pragma unroll
             for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float v = s[sb][r] * scale_log2;
-                    s[sb][r] = v;
-                    mx = fmaxf(mx, v);
-                }
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        float m_new = fmaxf(m_run, mx);
+        float m_new = fmaxf(m_run, mx * scale_log2);
         float alpha = fast_exp2(m_run - m_new);
         m_run = m_new;
         float psum = 0.0f;
@@ -144,7 +141,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(
             for (int u = 0; u < 2; ++u) {
                 float p[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) p[j] = fast_exp2(s[sb][8 * u + j] - m_new);
+                for (int j = 0; j < 8; ++j) p[j] = fast_exp2(__builtin_fmaf(s[sb][8 * u + j], scale_log2, -m_new));
                 psum += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
                 pf[sb][u] = f16x8{(f16)p[0], (f16)p[1], (f16)p[2], (f16)p[3],
                                   (f16)p[4], (f16)p[5], (f16)p[6], (f16)p[7]};
@@ -258,7 +255,7 @@ __global__ __launch_bounds__(256) void colmass_kernel(
                 for (int r = 0; r < 16; ++r) {
                     int ql = 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
                     int qi = qt0 + ql;
-                    float p = fast_exp2(s[r] * scale_log2 - sm.lse[ql]);
+                    float p = fast_exp2(__builtin_fmaf(s[r], scale_log2, -sm.lse[ql]));
                     p = (key <= qi && qi < N) ? p : 0.0f;
                     bool vis = qi >= vis_begin && qi < vis_begin + Nv;
                     acc_vis += vis ? p : 0.0f;
@@ -269,7 +266,7 @@ __global__ __launch_bounds__(256) void colmass_kernel(
                 for (int r = 0; r < 16; ++r) {
                     int ql = 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
                     int qi = qt0 + ql;
-                    float p = fast_exp2(s[r] * scale_log2 - sm.lse[ql]);
+                    float p = fast_exp2(__builtin_fmaf(s[r], scale_log2, -sm.lse[ql]));
                     bool vis = qi >= vis_begin && qi < vis_begin + Nv;
                     acc_vis += vis ? p : 0.0f;
                     acc_txt += vis ? 0.0f : p;
