@@ -181,3 +181,23 @@ def test_layer_13b_high_resolution_shape(qb):
     assert_teacher_forced_exact(ref, got, shape, K)
     free = run_gpu(qb, L, shape, x, pos, K)
     check_free_running(ref, free, shape, K, W)
+
+
+def test_layer_serving_shape_batch16(qb):
+    """One whole layer at the batched-serving shape (batch 16 x (576 + 128) tokens of the 7B model,
+    budget 235 as at layer 2 of the stack schedule): 11264 rows through the QKV projection and
+    attention, 16 x 363 kept rows through the rest, teacher-forced bit-exact against the oracle,
+    then one decode step of the 16 sequences over the pruned cache."""
+    from test_gpu_layer import build_layer, run_gpu, assert_teacher_forced_exact
+    from test_gpu_decode import check_decode
+    base = wl.CONFIGS[1]
+    shape = wl.Shape("c4_layer", d=base.d, H=base.H, F=base.F, layers=1, B=16, Nv=576, Nt=128,
+                     n_outlier=base.n_outlier, vis_begin=0)
+    K = 235
+    W, L, cos, sin = build_layer(shape, 4)
+    x, pos = wl.hidden_state(shape, 4), wl.positions(shape)
+    ref = oracle.prefill_layer(W, x, pos, shape.B, shape.N, 0, shape.Nv, K, cos, sin, prune_mid=True)
+    got = run_gpu(qb, L, shape, x, pos, K, dict(o=ref["o"], z=ref["z"], cm_inter=ref["cm_inter"],
+                                                cm_intra=ref["cm_intra"]))
+    assert_teacher_forced_exact(ref, got, shape, K)
+    check_decode(qb, shape, 4, K, steps=1)
