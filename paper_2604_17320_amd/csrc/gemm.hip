@@ -419,8 +419,14 @@ __global__ __launch_bounds__(512) void w4a4_gemv16_kernel(
     const int om = 4 * (ol >> 4) + oreg, on = n0 + 16 * oj + (ol & 15);
     float y32 = 0.0f;
 
+    // The R x (16 NB) group scales of a round come in with ONE 8-byte load per lane of waves 0..NB-1
+    // (lane l: group l / 4 of the round, 4 columns) and reach the chain owners through LDS, transposed
+    // so that an owner reads its column's R scales as two 16-byte pieces: a vector-memory instruction
+    // costs a wave tens of issue cycles, and R of them per owner and round were a third of the round.
+    static_assert(R == 16, "the scale staging below is laid out for 16 groups per round");
+    __shared__ __align__(16) f16 scs[16 * NB][R];
     uint4 ra[U], rb[U][NB];
-    f16 rs[R];
+    uint2 rsv = make_uint2(0, 0);
     auto fetch = [&](int r0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -429,10 +435,9 @@ __global__ __launch_bounds__(512) void w4a4_gemv16_kernel(
 #pragma unroll
             for (int j = 0; j < NB; ++j) rb[u][j] = wp[((size_t)g * N + n0 + 16 * j + c) * 4 + q];
         }
-        if (owner) {
-#pragma unroll
-            for (int i = 0; i < R; ++i) rs[i] = sw[(size_t)min(r0 + i, G - 1) * N + on];
-        }
+        if (wave < NB)
+            rsv = *reinterpret_cast<const uint2 *>(sw + (size_t)min(r0 + (lane >> 2), G - 1) * N + n0 + 16 * wave +
+                                                   4 * (lane & 3));
     };
     fetch(0);
     for (int r0 = 0; r0 < G; r0 += R) {
@@ -449,9 +454,13 @@ __global__ __launch_bounds__(512) void w4a4_gemv16_kernel(
                 acc[u][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(as_i32x4(ahi), as_i32x4(bhi), acc[u][j], 0, 0, 0);
             }
         }
-        float sc[R];
+        if (wave < NB) {                            // this round's scales -> LDS, [column][group]
+            const int col = 16 * wave + 4 * (lane & 3), gi = lane >> 2;
+            Pack16 t;
+            t.u = make_uint4(rsv.x, rsv.y, 0, 0);
 #pragma unroll
-        for (int i = 0; i < R; ++i) sc[i] = r0 + i < G ? (float)rs[i] : 0.0f;
+            for (int e = 0; e < 4; ++e) scs[col + e][gi] = t.h[e];
+        }
         bool live[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) live[u] = r0 + 8 * u + wave < G;
@@ -464,8 +473,15 @@ __global__ __launch_bounds__(512) void w4a4_gemv16_kernel(
                 for (int i = 0; i < 4; ++i) accs[8 * u + wave][j][i][lane] = live[u] ? acc[u][j][i] : 0;
         __syncthreads();
         if (owner) {
+            Pack16 s0, s1;
+            const uint4 *sp = reinterpret_cast<const uint4 *>(&scs[16 * oj + (ol & 15)][0]);
+            s0.u = sp[0];
+            s1.u = sp[1];
 #pragma unroll
-            for (int i = 0; i < R; ++i) y32 = __builtin_fmaf((float)accs[i][oj][oreg][ol], sc[i], y32);
+            for (int i = 0; i < R; ++i) {
+                const float sc = r0 + i < G ? (float)(i < 8 ? s0.h[i] : s1.h[i - 8]) : 0.0f;
+                y32 = __builtin_fmaf((float)accs[i][oj][oreg][ol], sc, y32);
+            }
         }
         __syncthreads();
     }
